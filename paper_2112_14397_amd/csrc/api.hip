@@ -1,0 +1,229 @@
+// C ABI of the DTS-Gate MoE layer: argument validation, context, and hand-off to the kernel launchers.
+#include <new>
+
+#include "kernels.h"
+
+using namespace evomoe;
+
+struct evomoe_ctx {
+    Ctx c;
+};
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+evomoe_status check_shape(const evomoe_shape* s) {
+    if (!s) return EVOMOE_EINVAL;
+    if (s->T <= 0 || s->d <= 0 || s->E <= 0 || s->F <= 0 || s->P_cap <= 0) return EVOMOE_EINVAL;
+    if (s->dtype != EVOMOE_F32 && s->dtype != EVOMOE_BF16) return EVOMOE_EINVAL;
+    if (s->act != EVOMOE_RELU && s->act != EVOMOE_GELU_ERF) return EVOMOE_EINVAL;
+    if (s->E > 64) return EVOMOE_EUNSUPPORTED;
+    const int vec = s->dtype == EVOMOE_BF16 ? 8 : 4;
+    if (s->d % vec || s->F % vec) return EVOMOE_EUNSUPPORTED;
+    if ((int64_t)s->T * s->E > INT32_MAX || s->P_cap > INT32_MAX) return EVOMOE_EUNSUPPORTED;
+    return EVOMOE_OK;
+}
+
+#define REQUIRE_PTR(p) \
+    do { if (!(p) || !aligned16(p)) return EVOMOE_EINVAL; } while (0)
+#define OPTIONAL_PTR(p) \
+    do { if ((p) && !aligned16(p)) return EVOMOE_EINVAL; } while (0)
+#define CHECK_CTX_SHAPE()                                  \
+    do {                                                   \
+        if (!ctx) return EVOMOE_EINVAL;                    \
+        evomoe_status st_ = check_shape(shape);            \
+        if (st_ != EVOMOE_OK) return st_;                  \
+    } while (0)
+
+evomoe_status from_hip(hipError_t e) { return e == hipSuccess ? EVOMOE_OK : EVOMOE_EHIP; }
+
+// Make sure the context's histogram scratch holds `elems` ints (grows with a device allocation).
+evomoe_status ensure_scratch(Ctx& c, size_t elems) {
+    if (elems <= c.block_counts_elems) return EVOMOE_OK;
+    if (c.block_counts) {
+        if (hipStreamSynchronize(c.stream) != hipSuccess) return EVOMOE_EHIP;
+        if (hipFree(c.block_counts) != hipSuccess) return EVOMOE_EHIP;
+        c.block_counts = nullptr;
+        c.block_counts_elems = 0;
+    }
+    size_t want = elems < 65536 ? 65536 : elems;
+    if (hipMalloc(&c.block_counts, want * sizeof(int32_t)) != hipSuccess) return EVOMOE_EHIP;
+    c.block_counts_elems = want;
+    return EVOMOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+evomoe_status evomoe_create(evomoe_ctx** ctx_out, void* hip_stream) {
+    if (!ctx_out) return EVOMOE_EINVAL;
+    *ctx_out = nullptr;
+    evomoe_ctx* ctx = new (std::nothrow) evomoe_ctx();
+    if (!ctx) return EVOMOE_EHIP;
+    Ctx& c = ctx->c;
+    c.stream = (hipStream_t)hip_stream;
+    c.block_counts = nullptr;
+    c.block_counts_elems = 0;
+    c.status_dev = nullptr;
+    hipDeviceProp_t prop;
+    int32_t* small = nullptr;
+    if (hipGetDevice(&c.device) != hipSuccess || hipGetDeviceProperties(&prop, c.device) != hipSuccess ||
+        hipMalloc(&small, 256) != hipSuccess) {
+        delete ctx;
+        return EVOMOE_EHIP;
+    }
+    c.num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    c.status_dev = small;          // [0] status flag
+    c.ticket_dev = small + 32;     // own 128-byte line
+    if (hipMemsetAsync(small, 0, 256, c.stream) != hipSuccess ||
+        ensure_scratch(c, 65536) != EVOMOE_OK) {
+        (void)hipFree(small);
+        delete ctx;
+        return EVOMOE_EHIP;
+    }
+    *ctx_out = ctx;
+    return EVOMOE_OK;
+}
+
+evomoe_status evomoe_destroy(evomoe_ctx* ctx) {
+    if (!ctx) return EVOMOE_EINVAL;
+    (void)hipStreamSynchronize(ctx->c.stream);
+    if (ctx->c.block_counts) (void)hipFree(ctx->c.block_counts);
+    if (ctx->c.status_dev) (void)hipFree(ctx->c.status_dev);
+    delete ctx;
+    return EVOMOE_OK;
+}
+
+const char* evomoe_status_string(evomoe_status s) {
+    switch (s) {
+        case EVOMOE_OK: return "ok";
+        case EVOMOE_EINVAL: return "invalid argument";
+        case EVOMOE_EUNSUPPORTED: return "unsupported shape";
+        case EVOMOE_ECAPACITY: return "number of selected pairs exceeds P_cap";
+        case EVOMOE_EWORKSPACE: return "workspace missing or too small";
+        case EVOMOE_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+size_t evomoe_workspace_bytes(const evomoe_shape* shape) {
+    if (check_shape(shape) != EVOMOE_OK) return 0;
+    const size_t a = ffn_bwd_workspace_bytes(*shape), b = gate_bwd_workspace_bytes(*shape);
+    const size_t m = a > b ? a : b;
+    return (m + 255) & ~(size_t)255;
+}
+
+evomoe_status evomoe_dts_gate(evomoe_ctx* ctx, const evomoe_shape* shape, const void* x,
+                              const float* Wg, const float* bg, const float* noise, float tau,
+                              float threshold, float* gprime, float* gate_w, uint64_t* mask_bits,
+                              int32_t* counts, int32_t* k_per_token) {
+    CHECK_CTX_SHAPE();
+    REQUIRE_PTR(x); REQUIRE_PTR(Wg); REQUIRE_PTR(gprime); REQUIRE_PTR(mask_bits); REQUIRE_PTR(counts);
+    OPTIONAL_PTR(bg); OPTIONAL_PTR(noise); OPTIONAL_PTR(gate_w); OPTIONAL_PTR(k_per_token);
+    if (!(tau > 0.f) || !(threshold >= 0.f)) return EVOMOE_EINVAL;
+    evomoe_status st = ensure_scratch(ctx->c, (size_t)gate_blocks(ctx->c, *shape) * shape->E);
+    if (st != EVOMOE_OK) return st;
+    return from_hip(launch_dts_gate(ctx->c, *shape, x, Wg, bg, noise, tau, threshold, gprime, gate_w,
+                                    mask_bits, counts, k_per_token));
+}
+
+evomoe_status evomoe_dispatch(evomoe_ctx* ctx, const evomoe_shape* shape, const uint64_t* mask_bits,
+                              const float* scores, int32_t* expert_offsets, int32_t* pair_token,
+                              float* pair_gate, int32_t* tok_off, int32_t* tok_rows,
+                              int64_t* num_pairs, const void* x, void* x_perm) {
+    CHECK_CTX_SHAPE();
+    REQUIRE_PTR(mask_bits); REQUIRE_PTR(scores); REQUIRE_PTR(expert_offsets); REQUIRE_PTR(pair_token);
+    REQUIRE_PTR(pair_gate); REQUIRE_PTR(tok_off); REQUIRE_PTR(tok_rows); REQUIRE_PTR(num_pairs);
+    OPTIONAL_PTR(x); OPTIONAL_PTR(x_perm);
+    if (x_perm && !x) return EVOMOE_EINVAL;
+    const size_t nblk = dispatch_blocks(*shape);
+    evomoe_status st = ensure_scratch(ctx->c, nblk * shape->E + nblk);
+    if (st != EVOMOE_OK) return st;
+    return from_hip(launch_dispatch(ctx->c, *shape, mask_bits, scores, expert_offsets, pair_token,
+                                    pair_gate, tok_off, tok_rows, num_pairs, x, x_perm));
+}
+
+evomoe_status evomoe_expert_ffn(evomoe_ctx* ctx, const evomoe_shape* shape, const void* x,
+                                const int32_t* pair_token, const int32_t* expert_offsets,
+                                const void* W1, const float* b1, const void* W2, const float* b2,
+                                void* H, void* A, void* O) {
+    CHECK_CTX_SHAPE();
+    REQUIRE_PTR(x); REQUIRE_PTR(expert_offsets); REQUIRE_PTR(W1); REQUIRE_PTR(W2);
+    REQUIRE_PTR(H); REQUIRE_PTR(A); REQUIRE_PTR(O);
+    OPTIONAL_PTR(pair_token); OPTIONAL_PTR(b1); OPTIONAL_PTR(b2);
+    return from_hip(launch_expert_ffn(ctx->c, *shape, x, pair_token, expert_offsets, W1, b1, W2, b2, H, A, O));
+}
+
+evomoe_status evomoe_combine(evomoe_ctx* ctx, const evomoe_shape* shape, const void* O,
+                             const float* pair_gate, const int32_t* tok_off, const int32_t* tok_rows,
+                             void* y) {
+    CHECK_CTX_SHAPE();
+    REQUIRE_PTR(O); REQUIRE_PTR(pair_gate); REQUIRE_PTR(tok_off); REQUIRE_PTR(tok_rows); REQUIRE_PTR(y);
+    return from_hip(launch_combine(ctx->c, *shape, O, pair_gate, tok_off, tok_rows, y));
+}
+
+evomoe_status evomoe_combine_bwd(evomoe_ctx* ctx, const evomoe_shape* shape, const void* dy,
+                                 const void* O, const float* pair_gate, const int32_t* pair_token,
+                                 const int32_t* expert_offsets, void* dO, float* dG_pairs) {
+    CHECK_CTX_SHAPE();
+    REQUIRE_PTR(dy); REQUIRE_PTR(O); REQUIRE_PTR(pair_gate); REQUIRE_PTR(pair_token);
+    REQUIRE_PTR(expert_offsets); REQUIRE_PTR(dO); REQUIRE_PTR(dG_pairs);
+    return from_hip(launch_combine_bwd(ctx->c, *shape, dy, O, pair_gate, pair_token, expert_offsets, dO, dG_pairs));
+}
+
+evomoe_status evomoe_expert_ffn_bwd(evomoe_ctx* ctx, const evomoe_shape* shape, const void* dO,
+                                    const void* H, const void* A, const void* x,
+                                    const int32_t* pair_token, const int32_t* expert_offsets,
+                                    const void* W1, const void* W2, void* dW1, float* db1, void* dW2,
+                                    float* db2, void* dXp, int accumulate, void* workspace,
+                                    size_t workspace_bytes) {
+    CHECK_CTX_SHAPE();
+    REQUIRE_PTR(dO); REQUIRE_PTR(H); REQUIRE_PTR(A); REQUIRE_PTR(x); REQUIRE_PTR(expert_offsets);
+    REQUIRE_PTR(W1); REQUIRE_PTR(W2); REQUIRE_PTR(dXp);
+    OPTIONAL_PTR(pair_token); OPTIONAL_PTR(dW1); OPTIONAL_PTR(db1); OPTIONAL_PTR(dW2); OPTIONAL_PTR(db2);
+    if (!workspace || !aligned16(workspace) || workspace_bytes < ffn_bwd_workspace_bytes(*shape))
+        return EVOMOE_EWORKSPACE;
+    return from_hip(launch_expert_ffn_bwd(ctx->c, *shape, dO, H, A, x, pair_token, expert_offsets, W1,
+                                          W2, dW1, db1, dW2, db2, dXp, accumulate, workspace));
+}
+
+evomoe_status evomoe_dispatch_bwd(evomoe_ctx* ctx, const evomoe_shape* shape, const void* dXp,
+                                  const int32_t* tok_off, const int32_t* tok_rows, void* dx) {
+    CHECK_CTX_SHAPE();
+    REQUIRE_PTR(dXp); REQUIRE_PTR(tok_off); REQUIRE_PTR(tok_rows); REQUIRE_PTR(dx);
+    return from_hip(launch_dispatch_bwd(ctx->c, *shape, dXp, tok_off, tok_rows, dx));
+}
+
+evomoe_status evomoe_dts_gate_bwd(evomoe_ctx* ctx, const evomoe_shape* shape, const float* dG_pairs,
+                                  const int32_t* tok_off, const int32_t* tok_rows, const float* gprime,
+                                  const uint64_t* mask_bits, float tau, const void* x, const float* Wg,
+                                  float* dWg, float* dbg, void* dx, void* workspace,
+                                  size_t workspace_bytes) {
+    CHECK_CTX_SHAPE();
+    REQUIRE_PTR(dG_pairs); REQUIRE_PTR(tok_off); REQUIRE_PTR(tok_rows); REQUIRE_PTR(gprime);
+    REQUIRE_PTR(mask_bits); REQUIRE_PTR(x); REQUIRE_PTR(Wg); REQUIRE_PTR(dWg); REQUIRE_PTR(dx);
+    OPTIONAL_PTR(dbg);
+    if (!(tau > 0.f)) return EVOMOE_EINVAL;
+    if (!workspace || !aligned16(workspace) || workspace_bytes < gate_bwd_workspace_bytes(*shape))
+        return EVOMOE_EWORKSPACE;
+    return from_hip(launch_dts_gate_bwd(ctx->c, *shape, dG_pairs, tok_off, tok_rows, gprime, mask_bits,
+                                        tau, x, Wg, dWg, dbg, dx, workspace));
+}
+
+evomoe_status evomoe_num_pairs(evomoe_ctx* ctx, const int64_t* num_pairs, int64_t* num_pairs_host) {
+    if (!ctx || !num_pairs || !num_pairs_host) return EVOMOE_EINVAL;
+    int32_t flag = 0;
+    if (hipMemcpyAsync(num_pairs_host, num_pairs, sizeof(int64_t), hipMemcpyDeviceToHost, ctx->c.stream) != hipSuccess ||
+        hipMemcpyAsync(&flag, ctx->c.status_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->c.stream) != hipSuccess ||
+        hipStreamSynchronize(ctx->c.stream) != hipSuccess)
+        return EVOMOE_EHIP;
+    if (flag & 1) {
+        if (hipMemsetAsync(ctx->c.status_dev, 0, sizeof(int32_t), ctx->c.stream) != hipSuccess) return EVOMOE_EHIP;
+        return EVOMOE_ECAPACITY;
+    }
+    return EVOMOE_OK;
+}
+
+}  // extern "C"

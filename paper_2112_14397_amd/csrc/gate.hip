@@ -1,0 +1,403 @@
+// DTS gate, forward and backward (EvoMoE Stage 2: Eq. gumbel_softmax, Eq. adaptive_sparsity, Algorithm 2).
+//
+// Forward, one launch: logits on the matrix cores (f32 MFMA, so products and sums keep float32
+// accuracy: a selection decided by g' > c must not move), + bias + Gumbel noise, temperature softmax,
+// strict threshold with the arg-max fallback, bit mask, per-token k, and the per-expert histogram
+// (per-block partial counts; the last block to finish adds them up in block order).
+#include "kernels.h"
+
+namespace evomoe {
+
+// ---------------------------------------------------------------------------------------------
+// forward
+// ---------------------------------------------------------------------------------------------
+// Block = 4 waves.  The block owns 16*RT consecutive tokens; each wave takes every 4th K-slab of all
+// of them (v_mfma_f32_16x16x4_f32: A = 16 tokens x 4 k, B = 4 k x 16 experts), the four partial
+// logit tiles are added in wave order through LDS, then 16/RT threads per token do the softmax.
+template <typename TX, int NE, int RT>
+__global__ __launch_bounds__(256) void dts_gate_kernel(
+    const TX* __restrict__ x, const float* __restrict__ Wg, const float* __restrict__ bg,
+    const float* __restrict__ noise, float tau, float c, int T, int d, int E,
+    float* __restrict__ gprime, float* __restrict__ gate_w, uint64_t* __restrict__ mask_bits,
+    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts,
+    int32_t* __restrict__ ticket, int32_t* __restrict__ counts)
+{
+    constexpr int KV = Elem<TX>::kVec;     // k's per 16-byte load
+    constexpr int KB = 4 * KV;             // k's per slab (4 lane groups x KV)
+    constexpr int TPB = 16 * RT;           // tokens per block
+    constexpr int EP = 16 * NE;            // experts padded to MFMA tiles
+    constexpr int LDZ = EP + 4;            // LDS row stride (bank-conflict-free tile writes)
+    constexpr int TPT = 256 / TPB;         // threads per token in the softmax phase
+    constexpr int EPT = EP / TPT;          // experts per thread there
+
+    __shared__ float zsum[TPB * LDZ];
+    __shared__ int cnt[64];
+    __shared__ int part[4][64];
+    __shared__ int is_last;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i16 = lane & 15, q = lane >> 4;
+    const int t0 = blockIdx.x * TPB;
+
+    f32x4 acc[RT][NE];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int n = 0; n < NE; ++n) acc[rt][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int kb = wave * KB; kb < d; kb += 4 * KB) {
+        const int k0 = kb + q * KV;            // this lane group's first k
+        float a[RT][KV];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const int t = t0 + rt * 16 + i16;
+            if (t < T && k0 < d) {
+                Elem<TX>::load_vec(x + (size_t)t * d + k0, a[rt]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < KV; ++j) a[rt][j] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < KV; ++j) {
+            const int k = k0 + j;
+#pragma unroll
+            for (int n = 0; n < NE; ++n) {
+                const int e = n * 16 + i16;
+                const float b = (k < d && e < E) ? Wg[(size_t)k * E + e] : 0.f;
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                    acc[rt][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[rt][j], b, acc[rt][n], 0, 0, 0);
+            }
+        }
+    }
+
+    if (tid < 64) cnt[tid] = 0;
+    // add the four waves' partial tiles in wave order (fixed order => reproducible bits)
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int n = 0; n < NE; ++n)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int idx = (rt * 16 + 4 * q + r) * LDZ + n * 16 + i16;
+                        const float v = acc[rt][n][r];
+                        zsum[idx] = (w == 0) ? v : zsum[idx] + v;
+                    }
+        }
+        __syncthreads();
+    }
+
+    // ---- softmax / threshold: TPT threads per token ----
+    const int tl = tid / TPT, sub = tid % TPT;
+    const int t = t0 + tl;
+    const bool tok_ok = t < T;
+    float a[EPT];
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int e = sub + j * TPT;
+        float z = -INFINITY;
+        if (tok_ok && e < E) {
+            z = zsum[tl * LDZ + e];
+            if (bg) z += bg[e];
+            if (noise) z += noise[(size_t)t * E + e];
+            z = z / tau;
+        }
+        a[j] = z;
+        m = fmaxf(m, z);
+    }
+#pragma unroll
+    for (int o = TPT >> 1; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    float ssum = 0.f;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int e = sub + j * TPT;
+        a[j] = (tok_ok && e < E) ? expf(a[j] - m) : 0.f;
+        ssum += a[j];
+    }
+#pragma unroll
+    for (int o = TPT >> 1; o > 0; o >>= 1) ssum += __shfl_xor(ssum, o, 64);
+
+    uint64_t bits = 0;
+    float best = -1.f;
+    int best_e = 0x7fffffff;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int e = sub + j * TPT;
+        const float g = a[j] / ssum;
+        a[j] = g;
+        if (tok_ok && e < E) {
+            if (g > c) bits |= (1ull << e);
+            if (g > best) { best = g; best_e = e; }   // ascending e: keeps the lowest index on ties
+        }
+    }
+#pragma unroll
+    for (int o = TPT >> 1; o > 0; o >>= 1) {
+        bits |= __shfl_xor(bits, o, 64);
+        const float ob = __shfl_xor(best, o, 64);
+        const int oe = __shfl_xor(best_e, o, 64);
+        if (ob > best || (ob == best && oe < best_e)) { best = ob; best_e = oe; }
+    }
+    if (tok_ok && bits == 0) bits = 1ull << best_e;     // Algorithm 2: len(id_s) >= 1
+
+    if (tok_ok) {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            const int e = sub + j * TPT;
+            if (e < E) {
+                const bool sel = (bits >> e) & 1ull;
+                gprime[(size_t)t * E + e] = a[j];
+                if (gate_w) gate_w[(size_t)t * E + e] = sel ? a[j] : 0.f;
+                if (sel) atomicAdd(&cnt[e], 1);
+            }
+        }
+        if (sub == 0) {
+            mask_bits[t] = bits;
+            if (k_per_token) k_per_token[t] = __popcll(bits);
+        }
+    }
+    __syncthreads();
+
+    // ---- per-expert histogram: per-block partials, summed by the last block to arrive ----
+    if (tid < E) block_counts[(size_t)blockIdx.x * E + tid] = cnt[tid];
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        const int tk = atomicAdd(ticket, 1);
+        __threadfence();
+        is_last = (tk == (int)gridDim.x - 1);
+    }
+    __syncthreads();
+    if (is_last) {
+        const int e = tid & 63, p = tid >> 6;
+        int sum = 0;
+        if (e < E)
+            for (int b = p; b < (int)gridDim.x; b += 4)
+                sum += __hip_atomic_load(&block_counts[(size_t)b * E + e], __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+        part[p][e] = sum;
+        __syncthreads();
+        if (tid < E) counts[tid] = part[0][tid] + part[1][tid] + part[2][tid] + part[3][tid];
+        if (tid == 0) atomicExch(ticket, 0);     // ready for the next launch on this stream
+    }
+}
+
+static int pick_rt(const Ctx& c, int T) {
+    // as many tokens per block as still leaves >= 2 blocks per compute unit
+    for (int rt = 4; rt > 1; rt >>= 1)
+        if ((T + 16 * rt - 1) / (16 * rt) >= 2 * c.num_cu) return rt;
+    return 1;
+}
+
+int gate_blocks(const Ctx& c, const evomoe_shape& s) {
+    const int tpb = 16 * pick_rt(c, s.T);
+    return (s.T + tpb - 1) / tpb;
+}
+
+template <typename TX, int NE, int RT>
+static hipError_t gate_launch_t(const Ctx& c, const evomoe_shape& s, const void* x, const float* Wg,
+                                const float* bg, const float* noise, float tau, float thr,
+                                float* gprime, float* gate_w, uint64_t* mask_bits, int32_t* counts,
+                                int32_t* k_per_token) {
+    const int blocks = (s.T + 16 * RT - 1) / (16 * RT);
+    hipLaunchKernelGGL((dts_gate_kernel<TX, NE, RT>), dim3(blocks), dim3(256), 0, c.stream,
+                       (const TX*)x, Wg, bg, noise, tau, thr, s.T, s.d, s.E, gprime, gate_w,
+                       mask_bits, k_per_token, c.block_counts, c.ticket_dev, counts);
+    return hipGetLastError();
+}
+
+template <typename TX, int NE>
+static hipError_t gate_launch_rt(int rt, const Ctx& c, const evomoe_shape& s, const void* x,
+                                 const float* Wg, const float* bg, const float* noise, float tau,
+                                 float thr, float* gp, float* gw, uint64_t* mb, int32_t* cn, int32_t* kt) {
+    switch (rt) {
+        case 4: return gate_launch_t<TX, NE, 4>(c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
+        case 2: return gate_launch_t<TX, NE, 2>(c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
+        default: return gate_launch_t<TX, NE, 1>(c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
+    }
+}
+
+template <typename TX>
+static hipError_t gate_launch_ne(const Ctx& c, const evomoe_shape& s, const void* x, const float* Wg,
+                                 const float* bg, const float* noise, float tau, float thr, float* gp,
+                                 float* gw, uint64_t* mb, int32_t* cn, int32_t* kt) {
+    const int rt = pick_rt(c, s.T);
+    switch ((s.E + 15) / 16) {
+        case 1: return gate_launch_rt<TX, 1>(rt, c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
+        case 2: return gate_launch_rt<TX, 2>(rt, c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
+        case 3: return gate_launch_rt<TX, 3>(rt, c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
+        default: return gate_launch_rt<TX, 4>(rt, c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
+    }
+}
+
+hipError_t launch_dts_gate(const Ctx& c, const evomoe_shape& s, const void* x, const float* Wg,
+                           const float* bg, const float* noise, float tau, float threshold,
+                           float* gprime, float* gate_w, uint64_t* mask_bits, int32_t* counts,
+                           int32_t* k_per_token) {
+    if (s.dtype == EVOMOE_BF16)
+        return gate_launch_ne<bf16_t>(c, s, x, Wg, bg, noise, tau, threshold, gprime, gate_w,
+                                      mask_bits, counts, k_per_token);
+    return gate_launch_ne<float>(c, s, x, Wg, bg, noise, tau, threshold, gprime, gate_w, mask_bits,
+                                 counts, k_per_token);
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward
+// ---------------------------------------------------------------------------------------------
+// dz_sj = (g'_sj / tau) * (dG_sj - sum_i dG_si g'_si), with dG_si read from the token's rows
+// (tok_rows lists them in ascending expert id = ascending set bit of the mask).
+__global__ __launch_bounds__(256) void gate_dz_kernel(
+    const float* __restrict__ dG_pairs, const int32_t* __restrict__ tok_off,
+    const int32_t* __restrict__ tok_rows, const float* __restrict__ gprime,
+    const uint64_t* __restrict__ mask_bits, float tau, int T, int E, int64_t P_cap,
+    float* __restrict__ dz)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    const uint64_t bits = mask_bits[t];
+    const int64_t base = tok_off[t];
+    const float* gp = gprime + (size_t)t * E;
+    float inner = 0.f;
+    {
+        uint64_t b = bits;
+        int j = 0;
+        while (b) {
+            const int e = __ffsll((unsigned long long)b) - 1;
+            b &= b - 1;
+            const int64_t slot = base + j++;
+            if (slot < P_cap) {
+                const int r = tok_rows[slot];
+                inner += dG_pairs[r] * gp[e];
+            }
+        }
+    }
+    int j = 0;
+    for (int e = 0; e < E; ++e) {
+        float dg = 0.f;
+        if ((bits >> e) & 1ull) {
+            const int64_t slot = base + j++;
+            if (slot < P_cap) dg = dG_pairs[tok_rows[slot]];
+        }
+        dz[(size_t)t * E + e] = gp[e] / tau * (dg - inner);
+    }
+}
+
+// One block = TC tokens x 256 columns k of x.  Thread k keeps W_g[k,:] and a partial dWg[k,:] in
+// registers, walks the chunk's tokens:  dx[s,k] += <dz[s,:], W_g[k,:]>,  dWg_part[k,:] += x[s,k] dz[s,:].
+template <typename TX, int EP>
+__global__ __launch_bounds__(256) void gate_bwd_kernel(
+    const float* __restrict__ dz, const TX* __restrict__ x, const float* __restrict__ Wg,
+    int T, int d, int E, int TC, TX* __restrict__ dx, float* __restrict__ dWg_part,
+    float* __restrict__ dbg_part)
+{
+    extern __shared__ float sdz[];          // [TC][E]
+    const int chunk = blockIdx.x;
+    const int s0 = chunk * TC;
+    const int ns = min(TC, T - s0);
+    for (int i = threadIdx.x; i < ns * E; i += 256) sdz[i] = dz[(size_t)s0 * E + i];
+    __syncthreads();
+    const int k = blockIdx.y * 256 + threadIdx.x;
+    if (blockIdx.y == 0 && threadIdx.x < E) {     // bias gradient partial: sum_s dz[s,e]
+        float sb = 0.f;
+        for (int s = 0; s < ns; ++s) sb += sdz[s * E + threadIdx.x];
+        dbg_part[(size_t)chunk * E + threadIdx.x] = sb;
+    }
+    if (k >= d) return;
+    float w[EP], g[EP];
+#pragma unroll
+    for (int e = 0; e < EP; ++e) {
+        w[e] = (e < E) ? Wg[(size_t)k * E + e] : 0.f;
+        g[e] = 0.f;
+    }
+    for (int s = 0; s < ns; ++s) {
+        const size_t off = (size_t)(s0 + s) * d + k;
+        const float xv = Elem<TX>::load(x + off);
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < EP; ++e) {
+            if (e < E) {
+                const float z = sdz[s * E + e];
+                acc += z * w[e];
+                g[e] += xv * z;
+            }
+        }
+        Elem<TX>::store(dx + off, Elem<TX>::load(dx + off) + acc);
+    }
+#pragma unroll
+    for (int e = 0; e < EP; ++e)
+        if (e < E) dWg_part[((size_t)chunk * d + k) * E + e] = g[e];
+}
+
+// out[i] = sum over chunks (ascending) of part[chunk][i]
+__global__ __launch_bounds__(256) void sum_chunks_kernel(const float* __restrict__ part, int nchunk,
+                                                         size_t n, float* __restrict__ out)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int c = 0; c < nchunk; ++c) s += part[(size_t)c * n + i];
+    out[i] = s;
+}
+
+static int gate_bwd_chunk_tokens(const evomoe_shape& s) {
+    int tc = 64;
+    while ((s.T + tc - 1) / tc > 128) tc *= 2;
+    // LDS holds [TC][E] floats; stay within 64 KB
+    while ((size_t)tc * s.E * 4 > 60 * 1024 && tc > 16) tc /= 2;
+    return tc;
+}
+
+size_t gate_bwd_workspace_bytes(const evomoe_shape& s) {
+    const int tc = gate_bwd_chunk_tokens(s);
+    const size_t nchunk = (s.T + tc - 1) / tc;
+    return ((size_t)s.T * s.E + nchunk * ((size_t)s.d * s.E + s.E)) * sizeof(float);
+}
+
+template <typename TX>
+static hipError_t gate_bwd_t(const Ctx& c, const evomoe_shape& s, const float* dz, const void* x,
+                             const float* Wg, void* dx, float* dWg_part, float* dbg_part, int tc,
+                             int nchunk) {
+    dim3 grid(nchunk, (s.d + 255) / 256);
+    const size_t lds = (size_t)tc * s.E * sizeof(float);
+    const int ep = ((s.E + 15) / 16) * 16;
+#define EVOMOE_GB(EPV)                                                                           \
+    hipLaunchKernelGGL((gate_bwd_kernel<TX, EPV>), grid, dim3(256), lds, c.stream, dz,           \
+                       (const TX*)x, Wg, s.T, s.d, s.E, tc, (TX*)dx, dWg_part, dbg_part)
+    if (ep == 16) EVOMOE_GB(16);
+    else if (ep == 32) EVOMOE_GB(32);
+    else if (ep == 48) EVOMOE_GB(48);
+    else EVOMOE_GB(64);
+#undef EVOMOE_GB
+    return hipGetLastError();
+}
+
+hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float* dG_pairs,
+                               const int32_t* tok_off, const int32_t* tok_rows, const float* gprime,
+                               const uint64_t* mask_bits, float tau, const void* x, const float* Wg,
+                               float* dWg, float* dbg, void* dx, void* workspace) {
+    const int tc = gate_bwd_chunk_tokens(s);
+    const int nchunk = (s.T + tc - 1) / tc;
+    float* dz = (float*)workspace;
+    float* dWg_part = dz + (size_t)s.T * s.E;
+    float* dbg_part = dWg_part + (size_t)nchunk * s.d * s.E;
+    hipLaunchKernelGGL(gate_dz_kernel, dim3((s.T + 255) / 256), dim3(256), 0, c.stream, dG_pairs,
+                       tok_off, tok_rows, gprime, mask_bits, tau, s.T, s.E, s.P_cap, dz);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    err = (s.dtype == EVOMOE_BF16)
+              ? gate_bwd_t<bf16_t>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk)
+              : gate_bwd_t<float>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk);
+    if (err != hipSuccess) return err;
+    const size_t n = (size_t)s.d * s.E;
+    hipLaunchKernelGGL(sum_chunks_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, dWg_part,
+                       nchunk, n, dWg);
+    if (dbg)
+        hipLaunchKernelGGL(sum_chunks_kernel, dim3(1), dim3(256), 0, c.stream, dbg_part, nchunk,
+                           (size_t)s.E, dbg);
+    return hipGetLastError();
+}
+
+}  // namespace evomoe

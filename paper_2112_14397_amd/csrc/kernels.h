@@ -1,0 +1,46 @@
+// Host-side launchers of the gfx950 kernels (one per step of the layer).  Internal to the library.
+#pragma once
+#include "common.h"
+
+namespace evomoe {
+
+// gate.hip
+hipError_t launch_dts_gate(const Ctx& c, const evomoe_shape& s, const void* x, const float* Wg,
+                           const float* bg, const float* noise, float tau, float threshold,
+                           float* gprime, float* gate_w, uint64_t* mask_bits, int32_t* counts,
+                           int32_t* k_per_token);
+int gate_blocks(const Ctx& c, const evomoe_shape& s);   // grid size of the gate kernel (scratch rows)
+hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float* dG_pairs,
+                               const int32_t* tok_off, const int32_t* tok_rows, const float* gprime,
+                               const uint64_t* mask_bits, float tau, const void* x, const float* Wg,
+                               float* dWg, float* dbg, void* dx, void* workspace);
+size_t gate_bwd_workspace_bytes(const evomoe_shape& s);
+
+// dispatch.hip
+hipError_t launch_dispatch(const Ctx& c, const evomoe_shape& s, const uint64_t* mask_bits,
+                           const float* scores, int32_t* expert_offsets, int32_t* pair_token,
+                           float* pair_gate, int32_t* tok_off, int32_t* tok_rows, int64_t* num_pairs,
+                           const void* x, void* x_perm);
+int dispatch_blocks(const evomoe_shape& s);
+hipError_t launch_dispatch_bwd(const Ctx& c, const evomoe_shape& s, const void* dXp,
+                               const int32_t* tok_off, const int32_t* tok_rows, void* dx);
+
+// combine.hip
+hipError_t launch_combine(const Ctx& c, const evomoe_shape& s, const void* O, const float* pair_gate,
+                          const int32_t* tok_off, const int32_t* tok_rows, void* y);
+hipError_t launch_combine_bwd(const Ctx& c, const evomoe_shape& s, const void* dy, const void* O,
+                              const float* pair_gate, const int32_t* pair_token,
+                              const int32_t* expert_offsets, void* dO, float* dG_pairs);
+
+// ffn.hip
+hipError_t launch_expert_ffn(const Ctx& c, const evomoe_shape& s, const void* x,
+                             const int32_t* pair_token, const int32_t* expert_offsets, const void* W1,
+                             const float* b1, const void* W2, const float* b2, void* H, void* A, void* O);
+hipError_t launch_expert_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, const void* H,
+                                 const void* A, const void* x, const int32_t* pair_token,
+                                 const int32_t* expert_offsets, const void* W1, const void* W2,
+                                 void* dW1, float* db1, void* dW2, float* db2, void* dXp,
+                                 int accumulate, void* workspace);
+size_t ffn_bwd_workspace_bytes(const evomoe_shape& s);
+
+}  // namespace evomoe

@@ -3,15 +3,20 @@ import numpy as np
 
 
 def tol_ok(got, ref, rtol):
-    """Per-tensor tolerance used for every floating-point comparison:
-    |got - ref| <= rtol * (|ref| + rms(ref)).  Pure element-wise relative error
-    is undefined at zeros, so the tensor's RMS sets the floor."""
+    """Tolerance used for every floating-point comparison:
+    |got - ref| <= rtol * (|ref| + rms(ref row)).  Pure element-wise relative error is undefined at
+    zeros, and the rounding error of an accumulated element scales with the size of the operands that
+    went into it, which the elements of one row (last axis) share; so the row's RMS sets the floor.
+    Vectors use the RMS of the whole vector."""
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
     assert got.shape == ref.shape, (got.shape, ref.shape)
     if ref.size == 0:
         return True, 0.0
-    rms = float(np.sqrt(np.mean(ref * ref)))
+    if ref.ndim >= 2:
+        rms = np.sqrt(np.mean(ref * ref, axis=-1, keepdims=True))
+    else:
+        rms = float(np.sqrt(np.mean(ref * ref)))
     err = np.abs(got - ref)
     bound = rtol * (np.abs(ref) + rms)
     worst = float((err / np.maximum(bound, 1e-300)).max())

@@ -1,0 +1,46 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header declares,
+and rejects bad arguments on the host before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2112_14397_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "evomoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(evomoe_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_entry_point():
+    names = _declared()
+    assert set(names) == set(B.ENTRY_POINTS), (names, B.ENTRY_POINTS)
+    L = B.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings_and_workspace_query():
+    L = B.lib()
+    for s in (0, -1, -2, -3, -4, -5):
+        assert len(L.evomoe_status_string(s)) > 0
+    ok = B.make_shape(8192, 768, 16, 3072, "bf16", "gelu", 8192 * 16)
+    assert B.evomoe_workspace_bytes(ok) >= 8192 * 16 * 3072 * 2
+    for bad in (B.make_shape(0, 768, 16, 3072, "bf16", "gelu", 10),
+                B.make_shape(8, 768, 65, 3072, "bf16", "gelu", 10),
+                B.make_shape(8, 770, 16, 3072, "bf16", "gelu", 10)):
+        assert B.evomoe_workspace_bytes(bad) == 0
+
+
+def test_null_context_is_rejected_without_a_gpu():
+    L = B.lib()
+    s = B.make_shape(8, 8, 2, 8, "f32", "relu", 16)
+    assert L.evomoe_dts_gate(None, ctypes.byref(s), None, None, None, None, 1.0, 0.1, None, None, None, None, None) == B.EVOMOE_EINVAL
+    assert L.evomoe_combine(None, ctypes.byref(s), None, None, None, None, None) == B.EVOMOE_EINVAL
+    assert L.evomoe_destroy(None) == B.EVOMOE_EINVAL
+    assert L.evomoe_create(None, None) == B.EVOMOE_EINVAL

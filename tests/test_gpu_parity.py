@@ -1,0 +1,209 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Integers (mask, counts, offsets, indices) must be bit exact, except mask bits of pairs whose oracle score
+is within 1e-6 of the threshold (counted and reported); floats must satisfy
+|gpu - ref| <= rtol * (|ref| + rms(ref row)) with rtol 1e-5 (float32 layer) or 2e-2 (bf16 layer).
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_2112_14397_amd import synth  # noqa: E402
+
+
+def _harness():
+    import gpu_harness
+    return gpu_harness
+
+
+def _mk(name, T, d, E, F, act, dtype, c, seed, bias=0.02, gate_scale=1.0, bg0=0.0):
+    cfg = synth.LayerConfig(name, T=T, d=d, E=E, F=F, act=act, dtype=dtype, taus=(1.0,), threshold=c,
+                            seed=seed, bias_std=bias, gate_bias_e0=bg0)
+    inp = synth.make_layer_inputs(cfg)
+    if gate_scale != 1.0:
+        inp.Wg = (inp.Wg * gate_scale).astype(np.float32)
+    return cfg, inp
+
+
+# ---- config 1 exactly as specified: tiny fp32 forward, three temperatures --------------------------
+
+@pytest.mark.parametrize("tau", synth.CONFIGS["tiny"].taus)
+def test_config1_tiny_fp32_forward(tau):
+    h = _harness()
+    cfg = synth.CONFIGS["tiny"]
+    inp = synth.make_layer_inputs(cfg)
+    gl = h.GpuLayer(inp, backward=True)
+    rep = {}
+    fwd, P, band, flip = h.compare_forward(gl, inp, tau, cfg.threshold, rep)
+    print(f"tiny tau={tau}: P={P} band={band} flipped={flip}")
+    h.compare_backward(gl, inp, fwd, tau)      # not required by the config; isolates logic from bf16 rounding
+
+
+# ---- ragged shapes spanning several tiles with tails, both storage types -----------------------------
+
+RAGGED = [
+    # name            T    d    E   F    act     dtype  c     seed
+    ("f32-ragged",    333, 72,  5,  136, "gelu", "f32", 0.12, 101),
+    ("f32-relu",      517, 64,  16, 200, "relu", "f32", 0.04, 102),
+    ("bf16-ragged",   777, 136, 7,  264, "gelu", "bf16", 0.10, 103),
+    ("bf16-e33",      1030, 128, 33, 320, "relu", "bf16", 0.02, 104),
+    ("bf16-e64",      2100, 256, 64, 512, "gelu", "bf16", 0.012, 105),
+    ("f32-e64",       600, 64,  64, 128, "gelu", "f32", 0.012, 106),
+    ("bf16-e1",       130, 64,  1,  128, "gelu", "bf16", 0.5, 107),
+]
+
+
+@pytest.mark.parametrize("case", RAGGED, ids=[c[0] for c in RAGGED])
+@pytest.mark.parametrize("tau", [2.0, 0.4])
+def test_ragged_forward_backward(case, tau):
+    h = _harness()
+    name, T, d, E, F, act, dtype, c, seed = case
+    # W_g is scaled up so that routing depends on the tokens, not only on the noise.  The bf16 cases
+    # stay closer to the configs' N(0, 0.02) gate: the gate's share of dx carries the bf16 rounding of O
+    # multiplied by |W_g| / tau, so a much larger gate at low tau would exceed what bf16 storage can give.
+    cfg, inp = _mk(name, T, d, E, F, act, dtype, c, seed, gate_scale=8.0 if dtype == "f32" else 2.0)
+    gl = h.GpuLayer(inp)
+    rep = {}
+    fwd, P, band, flip = h.compare_forward(gl, inp, tau, c, rep)
+    ref, worsts = h.compare_backward(gl, inp, fwd, tau)
+    print(f"{name} tau={tau}: {rep} worst={ {k: round(v, 3) for k, v in worsts.items()} }")
+
+
+# ---- the limits the paper states -------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_dense_limit_all_experts(dtype):
+    h = _harness()
+    cfg, inp = _mk("dense", 260, 64, 8, 128, "gelu", dtype, 0.0, 201)
+    gl = h.GpuLayer(inp)
+    fwd, P, band, flip = h.compare_forward(gl, inp, 1e6, 0.0)
+    assert P == cfg.T * cfg.E
+    assert (h.np_of(gl.buf.counts) == cfg.T).all()
+    h.compare_backward(gl, inp, fwd, 1e6)
+
+
+def test_low_temperature_is_top1():
+    h = _harness()
+    cfg, inp = _mk("top1", 500, 64, 8, 128, "relu", "bf16", 0.1, 202, gate_scale=10.0)
+    gl = h.GpuLayer(inp)
+    fwd, P, band, flip = h.compare_forward(gl, inp, 1e-4, 0.1)
+    assert P == cfg.T and (h.np_of(gl.buf.k) == 1).all()
+    h.compare_backward(gl, inp, fwd, 1e-4)
+
+
+def test_fallback_keeps_argmax_expert():
+    h = _harness()
+    # c above 1/E at a high temperature: no score passes, every token falls back to its arg-max
+    cfg, inp = _mk("fallback", 300, 64, 8, 128, "gelu", "f32", 0.2, 203, gate_scale=10.0)
+    gl = h.GpuLayer(inp)
+    rep = {}
+    fwd, P, band, flip = h.compare_forward(gl, inp, 50.0, 0.2, rep)
+    assert rep["fallback"] == cfg.T and P == cfg.T
+
+
+def test_expert_with_no_tokens_and_skewed_load():
+    h = _harness()
+    cfg, inp = _mk("empty", 400, 64, 6, 128, "gelu", "bf16", 0.1, 204, gate_scale=5.0)
+    inp.bg = np.array([3.0, 0, -60.0, 0, 0, -60.0], np.float32)       # experts 2 and 5 never selected
+    gl = h.GpuLayer(inp)
+    fwd, P, band, flip = h.compare_forward(gl, inp, 0.7, 0.1)
+    cnt = h.np_of(gl.buf.counts)
+    assert cnt[2] == 0 and cnt[5] == 0 and cnt[0] > cnt[1]
+    ref, _ = h.compare_backward(gl, inp, fwd, 0.7)
+    assert not h.np_of(gl.buf.dW1)[2].any() and not h.np_of(gl.buf.dW2)[5].any()
+
+
+def test_no_noise_no_bias_pointers():
+    h = _harness()
+    cfg, inp = _mk("nonoise", 200, 64, 4, 128, "relu", "f32", 0.1, 205, bias=0.0, gate_scale=20.0)
+    inp.noise = np.zeros_like(inp.noise)
+    gl = h.GpuLayer(inp)
+    gl.noise = None
+    gl.params.b1 = None
+    gl.params.b2 = None
+    fwd, *_ = h.compare_forward(gl, inp, 1.0, 0.1)
+    h.compare_backward(gl, inp, fwd, 1.0)
+
+
+# ---- determinism, accumulate flag, x_perm, capacity ---------------------------------------------------
+
+def test_bitwise_reproducible_and_accumulate():
+    h = _harness()
+    cfg, inp = _mk("repro", 700, 128, 8, 256, "gelu", "bf16", 0.05, 301, gate_scale=6.0)
+    gl = h.GpuLayer(inp)
+    gl.forward(1.0, 0.05); gl.backward(1.0)
+    names = ("gprime", "mask_bits", "counts", "pair_token", "tok_rows", "H", "A", "O", "y",
+             "dO", "dG_pairs", "dXp", "dx", "dW1", "dW2", "db1", "db2", "dWg", "dbg")
+    first = {n: getattr(gl.buf, n).clone() for n in names}
+    gl.forward(1.0, 0.05); gl.backward(1.0)
+    for n in names:
+        assert torch.equal(first[n].view(torch.uint8), getattr(gl.buf, n).view(torch.uint8)), n
+    # accumulate: running backward again with accumulate=1 doubles the weight gradients
+    from paper_2112_14397_amd import binding as B
+    b = gl.buf
+    B.evomoe_expert_ffn_bwd(gl.ctx, gl.shape, b.dO, b.H, b.A, gl.x, b.pair_token, b.expert_offsets,
+                            gl.params.W1, gl.params.W2, b.dW1, b.db1, b.dW2, b.db2, b.dXp, True, b.workspace)
+    torch.cuda.synchronize()
+    for n in ("dW1", "dW2", "db1", "db2"):
+        ok, worst = h.tol_ok(h.np_of(getattr(b, n)), 2 * h.np_of(first[n]), 1e-2)
+        assert ok, (n, worst)
+
+
+def test_xperm_gather_and_pregathered_input():
+    h = _harness()
+    from paper_2112_14397_amd import binding as B
+    cfg, inp = _mk("xperm", 300, 64, 4, 128, "gelu", "bf16", 0.1, 302, gate_scale=6.0)
+    gl = h.GpuLayer(inp)
+    P = gl.forward(1.0, 0.1)
+    b = gl.buf
+    xp = torch.zeros(gl.shape.P_cap, cfg.d, dtype=torch.bfloat16, device="cuda")
+    B.evomoe_dispatch(gl.ctx, gl.shape, b.mask_bits, b.gprime, b.expert_offsets, b.pair_token, b.pair_gate,
+                      b.tok_off, b.tok_rows, b.num_pairs, gl.x, xp)
+    torch.cuda.synchronize()
+    assert torch.equal(xp[:P], gl.x[b.pair_token[:P].long()])
+    O1 = b.O.clone()
+    B.evomoe_expert_ffn(gl.ctx, gl.shape, xp, None, b.expert_offsets, gl.params.W1, gl.params.b1,
+                        gl.params.W2, gl.params.b2, b.H, b.A, b.O)
+    torch.cuda.synchronize()
+    assert torch.equal(O1[:P], b.O[:P])
+
+
+def test_capacity_overflow_is_reported_and_stays_in_bounds():
+    h = _harness()
+    from paper_2112_14397_amd import binding as B
+    cfg, inp = _mk("cap", 256, 64, 8, 128, "gelu", "f32", 0.0, 303)
+    gl = h.GpuLayer(inp, P_cap=300)
+    with pytest.raises(B.EvoMoEError) as ei:
+        gl.forward(1e6, 0.0)          # dense: P = 2048 > 300
+    assert ei.value.status == B.EVOMOE_ECAPACITY
+    gl.backward(1e6)                  # clamps to P_cap; must not fault
+    # the context is usable again afterwards
+    P = gl.forward(0.01, 0.5)
+    assert P == cfg.T
+
+
+def test_argument_errors():
+    h = _harness()
+    from paper_2112_14397_amd import binding as B
+    cfg, inp = _mk("args", 64, 64, 4, 64, "gelu", "f32", 0.1, 304)
+    gl = h.GpuLayer(inp)
+    b = gl.buf
+    bad = B.make_shape(64, 64, 65, 64, "f32", "gelu", 256)
+    with pytest.raises(B.EvoMoEError) as ei:
+        B.evomoe_dts_gate(gl.ctx, bad, gl.x, gl.params.Wg, None, None, 1.0, 0.1, b.gprime, None, b.mask_bits, b.counts, None)
+    assert ei.value.status == B.EVOMOE_EUNSUPPORTED
+    with pytest.raises(B.EvoMoEError) as ei:
+        B.evomoe_dts_gate(gl.ctx, gl.shape, gl.x, gl.params.Wg, None, None, 0.0, 0.1, b.gprime, None, b.mask_bits, b.counts, None)
+    assert ei.value.status == B.EVOMOE_EINVAL
+    with pytest.raises(B.EvoMoEError) as ei:
+        B.evomoe_dts_gate(gl.ctx, gl.shape, None, gl.params.Wg, None, None, 1.0, 0.1, b.gprime, None, b.mask_bits, b.counts, None)
+    assert ei.value.status == B.EVOMOE_EINVAL
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.EvoMoEError) as ei:
+        B.evomoe_expert_ffn_bwd(gl.ctx, gl.shape, b.dO, b.H, b.A, gl.x, b.pair_token, b.expert_offsets,
+                                gl.params.W1, gl.params.W2, b.dW1, b.db1, b.dW2, b.db2, b.dXp, False, small)
+    assert ei.value.status == B.EVOMOE_EWORKSPACE
