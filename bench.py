@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the DTS-Gate MoE layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config gpt] [--no-cpu-baseline]
+
+A "step" is one forward + backward pass of the whole layer (gate, dispatch, expert FFNs, combine and
+every backward step) over one batch of T synthetic tokens, inputs already resident in HBM.  Successive
+steps walk the config's dense-to-sparse temperature sweep (tau 2.0 -> 0.3), so K steps cover each
+temperature K / len(sweep) times.  Prints ONE JSON line.
+
+The metric is MoE-layer tokens/s forward+backward on the GPT-shaped layer (d=768, E=16, T=8192), with
+the roofline fraction of the dominant kernel (bf16 MFMA) measured live with HIP events, and the CPU oracle
+timed on the host cores on a bounded sample of the same workload as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16
+PEAK_FP32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def _gemm_kernels():
+    # expert-FFN GEMM kernels: each does 2*P*d*F flops per launch
+    return ("ffn_gemm1", "ffn_gemm2", "ffn_bwd_dh", "ffn_bwd_dx", "ffn_bwd_dw2", "ffn_bwd_dw1")
+
+
+def cpu_baseline(cfg, inp, n_tokens, taus):
+    """The oracle as it stands, timed on the host cores on the first n_tokens tokens over the sweep."""
+    import numpy as np
+    from oracle import evomoe_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    x, noise, dy = inp.x[:n_tokens], inp.noise[:n_tokens], inp.dy[:n_tokens]
+    t0 = time.perf_counter()
+    pairs = 0
+    for tau in taus:
+        fwd = orc.moe_layer_forward(x, inp.Wg, inp.bg, noise, tau, cfg.threshold, inp.W1, inp.b1,
+                                    inp.W2, inp.b2, cfg.act)
+        orc.moe_layer_backward(fwd, dy, x, inp.Wg, tau, inp.W1, inp.W2, cfg.act)
+        pairs += int(fwd.disp.expert_offsets[-1])
+    dt = time.perf_counter() - t0
+    return {"value": n_tokens * len(taus) / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {n_tokens} tokens of the workload, fwd+bwd at each of the {len(taus)} sweep "
+                      f"temperatures ({pairs} pairs, {dt:.1f} s, float64 numpy)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=12)
+    ap.add_argument("--config", default="gpt")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=1024)
+    ap.add_argument("--profile-all", action="store_true",
+                    help="also time every kernel with events in a second pass (adds 'kernels' to the JSON)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (all experts resident, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2112_14397_amd import binding as B
+    from paper_2112_14397_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    inp = synth.make_layer_inputs(cfg)
+    dt = B.torch_dtype(cfg.dtype)
+    dev = lambda a, t=None: None if a is None else (torch.from_numpy(np.ascontiguousarray(a)).cuda().to(t) if t
+                                                    else torch.from_numpy(np.ascontiguousarray(a)).cuda())
+    x, noise, dy = dev(inp.x, dt), dev(inp.noise), dev(inp.dy, dt)
+    params = B.LayerParams(Wg=dev(inp.Wg), bg=dev(inp.bg), W1=dev(inp.W1, dt), b1=dev(inp.b1),
+                           W2=dev(inp.W2, dt), b2=dev(inp.b2))
+    ctx = B.Context()
+    taus = list(cfg.taus)
+
+    # size the per-pair buffers from the sweep's largest P (one untimed gate+dispatch per temperature)
+    probe_shape = B.make_shape(cfg.T, cfg.d, cfg.E, 8, cfg.dtype, cfg.act, cfg.T * cfg.E)
+    pb = B.LayerBuffers(probe_shape, backward=False)
+    P_of = {}
+    for tau in taus:
+        B.evomoe_dts_gate(ctx, probe_shape, x, params.Wg, params.bg, noise, tau, cfg.threshold, pb.gprime, None,
+                          pb.mask_bits, pb.counts, pb.k)
+        B.evomoe_dispatch(ctx, probe_shape, pb.mask_bits, pb.gprime, pb.expert_offsets, pb.pair_token,
+                          pb.pair_gate, pb.tok_off, pb.tok_rows, pb.num_pairs)
+        P_of[tau] = B.evomoe_num_pairs(ctx, pb.num_pairs)
+    del pb
+    P_cap = int(max(P_of.values()) * 1.02) + 256
+    shape = B.make_shape(cfg.T, cfg.d, cfg.E, cfg.F, cfg.dtype, cfg.act, P_cap)
+    buf = B.LayerBuffers(shape, backward=True)
+
+    def step(tau):
+        B.layer_forward(ctx, buf, params, x, noise, tau, cfg.threshold, write_gate_w=False)
+        B.layer_backward(ctx, buf, params, x, dy, tau)
+
+    for i in range(args.warmup):
+        step(taus[i % len(taus)])
+    torch.cuda.synchronize()
+
+    dominant = "ffn_bwd_dh"
+    B.evomoe_profile_select(ctx, dominant)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(taus[i % len(taus)])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = B.evomoe_profile_read(ctx)
+    B.evomoe_profile_select(ctx, None)
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    tokens_per_s = cfg.T * args.steps / elapsed
+    flops_per_pair_gemm = 2.0 * cfg.d * cfg.F
+    P_steps = [P_of[taus[i % len(taus)]] for i in range(args.steps)]
+    dom_ms, dom_n = prof.get(dominant, (0.0, 0))
+    dom_flops = sum(P_steps) * flops_per_pair_gemm
+    achieved = dom_flops / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
+    roofline = {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                "avg_launch_us": dom_ms * 1e3 / max(dom_n, 1), "launches": dom_n,
+                "flops_per_launch": "2*P*d*F, P = pairs at the step's temperature"}
+
+    out = {
+        "metric": "MoE-layer tokens/s fwd+bwd (d=768,E=16,T=8192) vs tau",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} F={cfg.F} {cfg.act} "
+                               f"c={cfg.threshold}, tau sweep {[round(t, 3) for t in taus]} (one tau per step, cyclic)",
+                   "pairs_per_tau": {f"{t:.3f}": P_of[t] for t in taus}, "P_cap": P_cap},
+        "layer_tflops": 6.0 * flops_per_pair_gemm * sum(P_steps) / elapsed / 1e12,
+        "roofline": roofline,
+    }
+
+    # per-temperature throughput (each temperature timed on its own, a few repeats)
+    per_tau = []
+    for tau in taus:
+        for _ in range(2):
+            step(tau)
+        torch.cuda.synchronize()
+        reps = 5
+        t1 = time.perf_counter()
+        for _ in range(reps):
+            step(tau)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t1) * 1e3 / reps
+        per_tau.append({"tau": round(tau, 3), "pairs": P_of[tau], "ms": ms, "tokens_per_s": cfg.T / ms * 1e3,
+                        "tflops": 6.0 * flops_per_pair_gemm * P_of[tau] / ms / 1e9})
+    out["per_tau"] = per_tau
+
+    if args.profile_all:
+        B.evomoe_profile_select(ctx, "all")
+        for i in range(len(taus) * 3):
+            step(taus[i % len(taus)])
+        allp = B.evomoe_profile_read(ctx)
+        B.evomoe_profile_select(ctx, None)
+        Psum = sum(P_of[t] for t in taus) * 3
+        ks = {}
+        for name, (ms, n) in allp.items():
+            ent = {"avg_us": ms * 1e3 / n, "launches": n}
+            if name in _gemm_kernels():
+                ent["tflops"] = Psum * flops_per_pair_gemm / (ms * 1e-3) / 1e12
+            ks[name] = ent
+        out["kernels"] = ks
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, inp, min(args.cpu_tokens, cfg.T), taus)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

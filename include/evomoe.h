@@ -171,6 +171,22 @@ evomoe_status evomoe_dts_gate_bwd(evomoe_ctx* ctx, const evomoe_shape* shape,
 /* Copies P to the host and reports a pending capacity overflow.  The only synchronising call. */
 evomoe_status evomoe_num_pairs(evomoe_ctx* ctx, const int64_t* num_pairs, int64_t* num_pairs_host);
 
+/* ---- measurement aid (not part of the layer) ----------------------------------------------------
+ * Times kernels with HIP events recorded around their launches on the context's own stream.
+ * evomoe_profile_select(ctx, id): id = one evomoe_kernel_id -> only that kernel is bracketed;
+ * EVOMOE_K_ALL -> every kernel; EVOMOE_K_NONE -> off (default).  Events accumulate until read.
+ * evomoe_profile_read synchronises the stream, writes per-kernel totals (milliseconds) and launch
+ * counts into host arrays of EVOMOE_K_COUNT entries, and clears the record. */
+typedef enum {
+    EVOMOE_K_GATE = 0, EVOMOE_K_DISPATCH_HIST, EVOMOE_K_DISPATCH_SCATTER, EVOMOE_K_FFN_GEMM1,
+    EVOMOE_K_FFN_GEMM2, EVOMOE_K_COMBINE, EVOMOE_K_COMBINE_BWD, EVOMOE_K_FFN_BWD_DH,
+    EVOMOE_K_FFN_BWD_DX, EVOMOE_K_FFN_BWD_DW2, EVOMOE_K_FFN_BWD_DW1, EVOMOE_K_FFN_BWD_DB,
+    EVOMOE_K_DISPATCH_BWD, EVOMOE_K_GATE_BWD_DZ, EVOMOE_K_GATE_BWD_MAIN, EVOMOE_K_GATE_BWD_REDUCE,
+    EVOMOE_K_COUNT, EVOMOE_K_ALL = -2, EVOMOE_K_NONE = -1
+} evomoe_kernel_id;
+evomoe_status evomoe_profile_select(evomoe_ctx* ctx, int kernel_id);
+evomoe_status evomoe_profile_read(evomoe_ctx* ctx, double* total_ms_host, int64_t* launches_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,8 +24,13 @@ ENTRY_POINTS = (
     "evomoe_create", "evomoe_destroy", "evomoe_status_string", "evomoe_workspace_bytes",
     "evomoe_dts_gate", "evomoe_dispatch", "evomoe_expert_ffn", "evomoe_combine",
     "evomoe_combine_bwd", "evomoe_expert_ffn_bwd", "evomoe_dispatch_bwd", "evomoe_dts_gate_bwd",
-    "evomoe_num_pairs",
+    "evomoe_num_pairs", "evomoe_profile_select", "evomoe_profile_read",
 )
+
+KERNEL_IDS = ("gate", "dispatch_hist", "dispatch_scatter", "ffn_gemm1", "ffn_gemm2", "combine", "combine_bwd",
+              "ffn_bwd_dh", "ffn_bwd_dx", "ffn_bwd_dw2", "ffn_bwd_dw1", "ffn_bwd_db", "dispatch_bwd",
+              "gate_bwd_dz", "gate_bwd_main", "gate_bwd_reduce")
+EVOMOE_K_ALL, EVOMOE_K_NONE = -2, -1
 
 
 class EvoMoEError(RuntimeError):
@@ -68,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.evomoe_dispatch_bwd.argtypes = [vp, sp] + [vp] * 4
         L.evomoe_dts_gate_bwd.argtypes = [vp, sp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, vp, sz]
         L.evomoe_num_pairs.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int64)]
+        L.evomoe_profile_select.argtypes = [vp, i32]
+        L.evomoe_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
         for n in ENTRY_POINTS:
             if n not in ("evomoe_status_string", "evomoe_workspace_bytes"):
                 getattr(L, n).restype = i32
@@ -175,6 +182,21 @@ def evomoe_num_pairs(ctx, num_pairs) -> int:
     out = ctypes.c_int64(0)
     _chk(lib().evomoe_num_pairs(ctx._h, _p(num_pairs), ctypes.byref(out)), "evomoe_num_pairs")
     return int(out.value)
+
+
+def evomoe_profile_select(ctx, kernel) -> None:
+    """kernel: a name from KERNEL_IDS, "all" or None (off)."""
+    kid = EVOMOE_K_NONE if kernel is None else EVOMOE_K_ALL if kernel == "all" else KERNEL_IDS.index(kernel)
+    _chk(lib().evomoe_profile_select(ctx._h, kid), "evomoe_profile_select")
+
+
+def evomoe_profile_read(ctx) -> dict:
+    """{kernel name: (total milliseconds, launches)} for the kernels bracketed since the last read."""
+    n = len(KERNEL_IDS)
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    _chk(lib().evomoe_profile_read(ctx._h, ms, cnt), "evomoe_profile_read")
+    return {KERNEL_IDS[i]: (float(ms[i]), int(cnt[i])) for i in range(n) if cnt[i]}
 
 
 # ---- buffers for one layer + the call sequence (allocation and ordering only) -------------------

@@ -67,6 +67,7 @@ evomoe_status evomoe_create(evomoe_ctx** ctx_out, void* hip_stream) {
     c.block_counts = nullptr;
     c.block_counts_elems = 0;
     c.status_dev = nullptr;
+    c.prof = nullptr;
     hipDeviceProp_t prop;
     int32_t* small = nullptr;
     if (hipGetDevice(&c.device) != hipSuccess || hipGetDeviceProperties(&prop, c.device) != hipSuccess ||
@@ -92,6 +93,14 @@ evomoe_status evomoe_destroy(evomoe_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->c.stream);
     if (ctx->c.block_counts) (void)hipFree(ctx->c.block_counts);
     if (ctx->c.status_dev) (void)hipFree(ctx->c.status_dev);
+    if (ctx->c.prof) {
+        for (int i = 0; i < ctx->c.prof->cap; ++i) {
+            (void)hipEventDestroy(ctx->c.prof->rec[i].start);
+            (void)hipEventDestroy(ctx->c.prof->rec[i].stop);
+        }
+        delete[] ctx->c.prof->rec;
+        delete ctx->c.prof;
+    }
     delete ctx;
     return EVOMOE_OK;
 }
@@ -223,6 +232,48 @@ evomoe_status evomoe_num_pairs(evomoe_ctx* ctx, const int64_t* num_pairs, int64_
         if (hipMemsetAsync(ctx->c.status_dev, 0, sizeof(int32_t), ctx->c.stream) != hipSuccess) return EVOMOE_EHIP;
         return EVOMOE_ECAPACITY;
     }
+    return EVOMOE_OK;
+}
+
+evomoe_status evomoe_profile_select(evomoe_ctx* ctx, int kernel_id) {
+    if (!ctx) return EVOMOE_EINVAL;
+    if (kernel_id != EVOMOE_K_ALL && kernel_id != EVOMOE_K_NONE && (kernel_id < 0 || kernel_id >= EVOMOE_K_COUNT))
+        return EVOMOE_EINVAL;
+    Ctx& c = ctx->c;
+    if (!c.prof) {
+        if (kernel_id == EVOMOE_K_NONE) return EVOMOE_OK;
+        Prof* p = new (std::nothrow) Prof();
+        if (!p) return EVOMOE_EHIP;
+        p->cap = 16384;
+        p->used = 0;
+        p->rec = new (std::nothrow) ProfRecord[p->cap];
+        if (!p->rec) { delete p; return EVOMOE_EHIP; }
+        for (int i = 0; i < p->cap; ++i) {
+            if (hipEventCreate(&p->rec[i].start) != hipSuccess || hipEventCreate(&p->rec[i].stop) != hipSuccess) {
+                p->cap = i;
+                break;
+            }
+        }
+        c.prof = p;
+    }
+    c.prof->select = kernel_id;
+    return EVOMOE_OK;
+}
+
+evomoe_status evomoe_profile_read(evomoe_ctx* ctx, double* total_ms_host, int64_t* launches_host) {
+    if (!ctx || !total_ms_host || !launches_host) return EVOMOE_EINVAL;
+    for (int i = 0; i < EVOMOE_K_COUNT; ++i) { total_ms_host[i] = 0.0; launches_host[i] = 0; }
+    Ctx& c = ctx->c;
+    if (!c.prof) return EVOMOE_OK;
+    if (hipStreamSynchronize(c.stream) != hipSuccess) return EVOMOE_EHIP;
+    for (int i = 0; i < c.prof->used; ++i) {
+        float ms = 0.f;
+        const ProfRecord& r = c.prof->rec[i];
+        if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) return EVOMOE_EHIP;
+        total_ms_host[r.id] += ms;
+        launches_host[r.id] += 1;
+    }
+    c.prof->used = 0;
     return EVOMOE_OK;
 }
 

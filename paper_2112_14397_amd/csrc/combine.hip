@@ -38,6 +38,7 @@ hipError_t launch_combine(const Ctx& c, const evomoe_shape& s, const void* O, co
     const int64_t total = (int64_t)s.T * (s.d / kv);
     const int64_t want = (total + 255) / 256, cap = (int64_t)c.num_cu * 16;
     const int blocks = (int)(want < cap ? want : cap);
+    ProfScope ps(c, EVOMOE_K_COMBINE);
     if (s.dtype == EVOMOE_BF16)
         hipLaunchKernelGGL(combine_kernel<bf16_t>, dim3(blocks), dim3(256), 0, c.stream,
                            (const bf16_t*)O, pair_gate, tok_off, tok_rows, s.T, s.d, s.P_cap, (bf16_t*)y);
@@ -85,6 +86,7 @@ hipError_t launch_combine_bwd(const Ctx& c, const evomoe_shape& s, const void* d
                               const int32_t* expert_offsets, void* dO, float* dG_pairs) {
     const int64_t want = (s.P_cap + 3) / 4, cap = (int64_t)c.num_cu * 16;
     const int blocks = (int)(want < cap ? want : cap);
+    ProfScope ps(c, EVOMOE_K_COMBINE_BWD);
     if (s.dtype == EVOMOE_BF16)
         hipLaunchKernelGGL(combine_bwd_kernel<bf16_t>, dim3(blocks), dim3(256), 0, c.stream,
                            (const bf16_t*)dy, (const bf16_t*)O, pair_gate, pair_token, expert_offsets,

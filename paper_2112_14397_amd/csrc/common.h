@@ -93,6 +93,14 @@ __device__ __forceinline__ int clamp_pairs(int P, int64_t P_cap) {
     return (int64_t)P > P_cap ? (int)P_cap : P;
 }
 
+// Optional per-kernel timing with HIP events on the context's stream (measurement aid).
+struct ProfRecord { int id; hipEvent_t start, stop; };
+struct Prof {
+    int select;                       // evomoe_kernel_id, EVOMOE_K_ALL or EVOMOE_K_NONE
+    ProfRecord* rec;                  // pool
+    int used, cap;
+};
+
 struct Ctx {
     hipStream_t stream;
     int device;
@@ -101,6 +109,22 @@ struct Ctx {
     int32_t* ticket_dev;      // [1] arrival counter of the gate's last-block reduction
     int32_t* block_counts;    // scratch for per-block expert histograms
     size_t block_counts_elems;
+    Prof* prof;
+};
+
+// Brackets the kernel launches issued during its lifetime with two events when kernel `id` is selected.
+struct ProfScope {
+    const Ctx& c;
+    ProfRecord* r;
+    ProfScope(const Ctx& ctx, int id) : c(ctx), r(nullptr) {
+        Prof* p = ctx.prof;
+        if (!p || p->select == EVOMOE_K_NONE || (p->select != EVOMOE_K_ALL && p->select != id)) return;
+        if (p->used >= p->cap) return;
+        r = &p->rec[p->used++];
+        r->id = id;
+        (void)hipEventRecord(r->start, ctx.stream);
+    }
+    ~ProfScope() { if (r) (void)hipEventRecord(r->stop, c.stream); }
 };
 
 }  // namespace evomoe

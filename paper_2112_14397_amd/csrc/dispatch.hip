@@ -151,11 +151,17 @@ hipError_t launch_dispatch(const Ctx& c, const evomoe_shape& s, const uint64_t* 
     const int nblk = dispatch_blocks(s);
     int32_t* base = c.block_counts;
     int32_t* tok_base = c.block_counts + (size_t)nblk * s.E;
-    hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, s.T, s.E,
-                       s.P_cap, base, tok_base, c.ticket_dev, expert_offsets, tok_off, num_pairs,
-                       c.status_dev);
-    hipLaunchKernelGGL(dispatch_scatter_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, scores,
-                       s.T, s.E, s.P_cap, base, tok_base, pair_token, pair_gate, tok_off, tok_rows);
+    {
+        ProfScope ps(c, EVOMOE_K_DISPATCH_HIST);
+        hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, s.T, s.E,
+                           s.P_cap, base, tok_base, c.ticket_dev, expert_offsets, tok_off, num_pairs,
+                           c.status_dev);
+    }
+    {
+        ProfScope ps(c, EVOMOE_K_DISPATCH_SCATTER);
+        hipLaunchKernelGGL(dispatch_scatter_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, scores,
+                           s.T, s.E, s.P_cap, base, tok_base, pair_token, pair_gate, tok_off, tok_rows);
+    }
     if (x_perm) {
         const int esz = s.dtype == EVOMOE_BF16 ? 2 : 4;
         const int vec_per_row = s.d * esz / 16;
@@ -200,6 +206,7 @@ hipError_t launch_dispatch_bwd(const Ctx& c, const evomoe_shape& s, const void* 
     const int64_t total = (int64_t)s.T * (s.d / kv);
     const int blocks = (int)((total + 255) / 256 < (int64_t)c.num_cu * 16 ? (total + 255) / 256
                                                                            : (int64_t)c.num_cu * 16);
+    ProfScope ps(c, EVOMOE_K_DISPATCH_BWD);
     if (s.dtype == EVOMOE_BF16)
         hipLaunchKernelGGL(dispatch_bwd_kernel<bf16_t>, dim3(blocks), dim3(256), 0, c.stream,
                            (const bf16_t*)dXp, tok_off, tok_rows, s.T, s.d, s.P_cap, (bf16_t*)dx);

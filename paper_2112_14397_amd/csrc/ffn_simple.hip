@@ -231,10 +231,12 @@ hipError_t simple_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, co
                           const void* W2, const float* b2, void* H, void* A, void* O) {
     const int gx = row_tile_grid(c, s);
     // H = X W1^T + b1, A = act(H):  B_g(k, n) = W1[g][n][k]
+    { ProfScope ps(c, EVOMOE_K_FFN_GEMM1);
     hipLaunchKernelGGL((ffn_rows_kernel<TX, EPI_HA>), dim3(gx, (s.F + BN - 1) / BN), dim3(256), 0, c.stream,
                        (const TX*)x, s.d, pair_token, expert_offsets, s.E, s.P_cap, (const TX*)W1,
-                       (int64_t)s.F * s.d, 1, s.d, s.F, s.d, b1, (const TX*)nullptr, (TX*)H, (TX*)A, s.act);
+                       (int64_t)s.F * s.d, 1, s.d, s.F, s.d, b1, (const TX*)nullptr, (TX*)H, (TX*)A, s.act); }
     // O = A W2^T + b2:  B_g(k, n) = W2[g][n][k]
+    ProfScope ps(c, EVOMOE_K_FFN_GEMM2);
     hipLaunchKernelGGL((ffn_rows_kernel<TX, EPI_BIAS>), dim3(gx, (s.d + BN - 1) / BN), dim3(256), 0, c.stream,
                        (const TX*)A, s.F, (const int32_t*)nullptr, expert_offsets, s.E, s.P_cap,
                        (const TX*)W2, (int64_t)s.d * s.F, 1, s.F, s.d, s.F, b2, (const TX*)nullptr,
@@ -249,25 +251,32 @@ hipError_t simple_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, c
                           float* db1, void* dW2, float* db2, void* dXp, int accumulate, void* dH) {
     const int gx = row_tile_grid(c, s);
     // dH = (dO W2) * act'(H):  B_g(k, n) = W2[g][k][n]
+    { ProfScope ps(c, EVOMOE_K_FFN_BWD_DH);
     hipLaunchKernelGGL((ffn_rows_kernel<TX, EPI_ACTGRAD>), dim3(gx, (s.F + BN - 1) / BN), dim3(256), 0,
                        c.stream, (const TX*)dO, s.d, (const int32_t*)nullptr, expert_offsets, s.E,
                        s.P_cap, (const TX*)W2, (int64_t)s.d * s.F, s.F, 1, s.F, s.d,
-                       (const float*)nullptr, (const TX*)H, (TX*)dH, (TX*)nullptr, s.act);
+                       (const float*)nullptr, (const TX*)H, (TX*)dH, (TX*)nullptr, s.act); }
     // dXp = dH W1:  B_g(k, n) = W1[g][k][n]
+    { ProfScope ps(c, EVOMOE_K_FFN_BWD_DX);
     hipLaunchKernelGGL((ffn_rows_kernel<TX, EPI_NONE>), dim3(gx, (s.d + BN - 1) / BN), dim3(256), 0,
                        c.stream, (const TX*)dH, s.F, (const int32_t*)nullptr, expert_offsets, s.E,
                        s.P_cap, (const TX*)W1, (int64_t)s.F * s.d, s.d, 1, s.d, s.F,
-                       (const float*)nullptr, (const TX*)nullptr, (TX*)dXp, (TX*)nullptr, s.act);
-    if (dW2)   // dW2_g = dO_g^T A_g   [d, F]
+                       (const float*)nullptr, (const TX*)nullptr, (TX*)dXp, (TX*)nullptr, s.act); }
+    if (dW2) { // dW2_g = dO_g^T A_g   [d, F]
+        ProfScope ps(c, EVOMOE_K_FFN_BWD_DW2);
         hipLaunchKernelGGL(ffn_wgrad_kernel<TX>, dim3((s.F + BN - 1) / BN, (s.d + BM - 1) / BM, s.E),
                            dim3(256), 0, c.stream, (const TX*)dO, s.d, (const TX*)A, s.F,
                            (const int32_t*)nullptr, expert_offsets, s.E, s.P_cap, (TX*)dW2, accumulate);
-    if (dW1)   // dW1_g = dH_g^T X_g    [F, d]
+    }
+    if (dW1) { // dW1_g = dH_g^T X_g    [F, d]
+        ProfScope ps(c, EVOMOE_K_FFN_BWD_DW1);
         hipLaunchKernelGGL(ffn_wgrad_kernel<TX>, dim3((s.d + BN - 1) / BN, (s.F + BM - 1) / BM, s.E),
                            dim3(256), 0, c.stream, (const TX*)dH, s.F, (const TX*)x, s.d, pair_token,
                            expert_offsets, s.E, s.P_cap, (TX*)dW1, accumulate);
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
+    ProfScope ps(c, EVOMOE_K_FFN_BWD_DB);
     if (db2) err = launch_colsum<TX>(c, s, dO, s.d, expert_offsets, db2, accumulate);
     if (err != hipSuccess) return err;
     if (db1) err = launch_colsum<TX>(c, s, dH, s.F, expert_offsets, db1, accumulate);

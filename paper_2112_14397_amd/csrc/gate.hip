@@ -203,6 +203,7 @@ static hipError_t gate_launch_t(const Ctx& c, const evomoe_shape& s, const void*
                                 float* gprime, float* gate_w, uint64_t* mask_bits, int32_t* counts,
                                 int32_t* k_per_token) {
     const int blocks = (s.T + 16 * RT - 1) / (16 * RT);
+    ProfScope ps(c, EVOMOE_K_GATE);
     hipLaunchKernelGGL((dts_gate_kernel<TX, NE, RT>), dim3(blocks), dim3(256), 0, c.stream,
                        (const TX*)x, Wg, bg, noise, tau, thr, s.T, s.d, s.E, gprime, gate_w,
                        mask_bits, k_per_token, c.block_counts, c.ticket_dev, counts);
@@ -383,15 +384,22 @@ hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float*
     float* dz = (float*)workspace;
     float* dWg_part = dz + (size_t)s.T * s.E;
     float* dbg_part = dWg_part + (size_t)nchunk * s.d * s.E;
-    hipLaunchKernelGGL(gate_dz_kernel, dim3((s.T + 255) / 256), dim3(256), 0, c.stream, dG_pairs,
-                       tok_off, tok_rows, gprime, mask_bits, tau, s.T, s.E, s.P_cap, dz);
+    {
+        ProfScope ps(c, EVOMOE_K_GATE_BWD_DZ);
+        hipLaunchKernelGGL(gate_dz_kernel, dim3((s.T + 255) / 256), dim3(256), 0, c.stream, dG_pairs,
+                           tok_off, tok_rows, gprime, mask_bits, tau, s.T, s.E, s.P_cap, dz);
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    err = (s.dtype == EVOMOE_BF16)
-              ? gate_bwd_t<bf16_t>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk)
-              : gate_bwd_t<float>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk);
+    {
+        ProfScope ps(c, EVOMOE_K_GATE_BWD_MAIN);
+        err = (s.dtype == EVOMOE_BF16)
+                  ? gate_bwd_t<bf16_t>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk)
+                  : gate_bwd_t<float>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk);
+    }
     if (err != hipSuccess) return err;
     const size_t n = (size_t)s.d * s.E;
+    ProfScope ps(c, EVOMOE_K_GATE_BWD_REDUCE);
     hipLaunchKernelGGL(sum_chunks_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, dWg_part,
                        nchunk, n, dWg);
     if (dbg)
