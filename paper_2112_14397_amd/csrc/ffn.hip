@@ -12,7 +12,7 @@ hipError_t launch_expert_ffn(const Ctx& c, const evomoe_shape& s, const void* x,
                              const int32_t* pair_token, const int32_t* expert_offsets, const void* W1,
                              const float* b1, const void* W2, const float* b2, void* H, void* A, void* O) {
     if (s.dtype == EVOMOE_BF16)
-        return simple_ffn_fwd<bf16_t>(c, s, x, pair_token, expert_offsets, W1, b1, W2, b2, H, A, O);
+        return mfma_ffn_fwd(c, s, x, pair_token, expert_offsets, W1, b1, W2, b2, H, A, O);
     return simple_ffn_fwd<float>(c, s, x, pair_token, expert_offsets, W1, b1, W2, b2, H, A, O);
 }
 
@@ -22,8 +22,8 @@ hipError_t launch_expert_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void
                                  void* dW1, float* db1, void* dW2, float* db2, void* dXp,
                                  int accumulate, void* workspace) {
     if (s.dtype == EVOMOE_BF16)
-        return simple_ffn_bwd<bf16_t>(c, s, dO, H, A, x, pair_token, expert_offsets, W1, W2, dW1, db1,
-                                      dW2, db2, dXp, accumulate, workspace);
+        return mfma_ffn_bwd(c, s, dO, H, A, x, pair_token, expert_offsets, W1, W2, dW1, db1, dW2, db2,
+                            dXp, accumulate, workspace);
     return simple_ffn_bwd<float>(c, s, dO, H, A, x, pair_token, expert_offsets, W1, W2, dW1, db1, dW2,
                                  db2, dXp, accumulate, workspace);
 }
