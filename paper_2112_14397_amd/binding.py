@@ -14,7 +14,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libevomoe.so")
+LIB_PATH = os.path.join(_HERE, "libevomoe.so")   # tests and tools may point this elsewhere before lib()
 
 EVOMOE_F32, EVOMOE_BF16 = 0, 1
 EVOMOE_RELU, EVOMOE_GELU_ERF = 0, 1

@@ -4,8 +4,7 @@
 namespace evomoe {
 
 size_t ffn_bwd_workspace_bytes(const evomoe_shape& s) {
-    const size_t esz = s.dtype == EVOMOE_BF16 ? 2 : 4;
-    return (size_t)s.P_cap * s.F * esz;      // dH
+    return dh_bytes(s) + colsum_scratch_bytes(s);
 }
 
 hipError_t launch_expert_ffn(const Ctx& c, const evomoe_shape& s, const void* x,

@@ -15,7 +15,13 @@ hipError_t simple_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, c
                           float* db1, void* dW2, float* db2, void* dXp, int accumulate, void* dH);
 template <typename TX>
 hipError_t launch_colsum(const Ctx& c, const evomoe_shape& s, const void* Mx, int N,
-                         const int32_t* expert_offsets, float* db, int accumulate);
+                         const int32_t* expert_offsets, float* db, int accumulate, float* scratch);
+size_t colsum_scratch_bytes(const evomoe_shape& s);
+// the backward workspace is [dH : P_cap x F elements, rounded up to 256 B][bias-gradient partial sums]
+inline size_t dh_bytes(const evomoe_shape& s) {
+    const size_t esz = s.dtype == EVOMOE_BF16 ? 2 : 4;
+    return ((size_t)s.P_cap * s.F * esz + 255) & ~(size_t)255;
+}
 
 // bf16 matrix-core path (ffn_mfma.hip)
 hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, const int32_t* pair_token,

@@ -5,20 +5,22 @@
 //   NN  C[r,n] = sum_k A[r,k]       * W_g[k,n]      dH = dO W2,  dXp = dH W1
 //   TN  C_g[m,n] = sum_{r in g} L[r,m] * R[rrow(r),n]   weight gradients (contraction over the ragged rows)
 //
-// Block = 4 waves (2 x 2), block tile BM x BN, K slab 64, double-buffered LDS, operands fetched with
-// 16-byte global loads.  Operands whose contraction index is contiguous in memory sit in LDS as
-// [row][64 k] with an XOR swizzle of the 16-byte chunks and are read with ds_read_b128; operands whose
-// contraction index is the row index sit as [k][cols] (padded rows) and are read with the transposing
-// LDS load (ds_read_b64_tr_b16), so no operand is ever transposed in global memory.
-// Epilogues (bias, activation, act'(H) product, accumulate) run in f32 on a row-major copy of the
-// accumulators staged through LDS, and leave with 16-byte stores.
+// Block = 4 waves (2 x 2), block tile BM x BN, K slabs of BK, NSTAGE LDS stages filled by direct
+// global->LDS loads (no staging registers) that run NSTAGE-1 slabs ahead of the MFMAs.  Operands whose
+// contraction index is contiguous in memory sit in LDS as [row][BK k] with an XOR swizzle of the 16-byte
+// chunks and are read with ds_read_b128; operands whose contraction index is the row index sit as
+// [k][cols] with a swizzle of 32-byte blocks and are read with the transposing LDS load
+// (ds_read_b64_tr_b16), so no operand is ever transposed in global memory.  The persistent grid walks
+// the tiles in an XCD-aware order.  Epilogues (bias, activation, act'(H) product, accumulate) run in f32
+// on a row-major copy of the accumulators staged through LDS, and leave with 16-byte stores.
+#include <type_traits>
+
 #include "ffn_internal.h"
 
 namespace evomoe {
 
 namespace {
 
-constexpr int BK = 64;
 enum { L_NT = 0, L_NN = 1, L_TN = 2 };
 enum { E_HA = 0, E_BIAS = 1, E_ACTGRAD = 2, E_NONE = 3, E_WGRAD = 4 };
 
@@ -43,36 +45,82 @@ struct GemmArgs {
 };
 
 // ---- LDS geometry -------------------------------------------------------------------------------
-// k-contiguous tile: [R][64] bf16, 128 B per row, 16-byte chunk c of row r stored at chunk c ^ (r & 7)
-__device__ __forceinline__ int kc_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
-// k-strided tile: [64][C] bf16, row stride C*2 + 32 bytes
-template <int C> __device__ __forceinline__ int ks_off(int k, int col) { return k * (C * 2 + 32) + col * 2; }
-template <int R> constexpr int kc_bytes() { return R * 128; }
-template <int C> constexpr int ks_bytes() { return 64 * (C * 2 + 32); }
-
-template <int LAYOUT, int BM, int BN> struct Geo {
+// Operand tiles are written by direct global->LDS loads (64 lanes x 16 B land contiguously), so a stage
+// is a dense array and bank conflicts are avoided by permuting 16-byte chunks on the global side:
+//  * k-contiguous tile [R][BK k] bf16: chunk c of row r sits at chunk c ^ key(r), key = r & 7 (BK = 64,
+//    128-byte rows) or (r >> 1) & 3 (BK = 32, 64-byte rows): eight consecutive rows reading the same
+//    k-chunk with ds_read_b128 touch eight different bank groups;
+//  * k-strided tile [BK k][C cols] bf16, 2C B per row: 32-byte block b of row k sits at block b ^ (k & 3)
+//    (the transposing read ds_read_b64_tr_b16 takes the same block from four consecutive k rows).
+template <int LAYOUT, int BM, int BN, int BK, int NSTAGE> struct Geo {
     static constexpr bool A_KC = (LAYOUT != L_TN);          // A operand k-contiguous?
     static constexpr bool B_KC = (LAYOUT == L_NT);
-    static constexpr int A_BYTES = A_KC ? kc_bytes<BM>() : ks_bytes<BM>();
-    static constexpr int B_BYTES = B_KC ? kc_bytes<BN>() : ks_bytes<BN>();
+    static constexpr int A_BYTES = BM * BK * 2;
+    static constexpr int B_BYTES = BN * BK * 2;
     static constexpr int STAGE = A_BYTES + B_BYTES;
     static constexpr int WM = BM / 2, WN = BN / 2;
-    static constexpr int EPI_ROWS = 64;                      // rows of the wave tile staged per pass
     static constexpr int EPI_LD = WN + 4;                    // f32 row stride of the staging copy
+    // rows of the wave tile staged per pass: as many as fit next to nothing else in the operand stages
+    static constexpr int EPI_ROWS = (WM >= 64 && 4 * 64 * EPI_LD * 4 <= NSTAGE * STAGE + 8192) ? 64 : 32;
     static constexpr int EPI_BYTES = 4 * EPI_ROWS * EPI_LD * 4;
-    static constexpr int SMEM = (2 * STAGE > EPI_BYTES ? 2 * STAGE : EPI_BYTES);
+    static constexpr int SMEM = (NSTAGE * STAGE > EPI_BYTES ? NSTAGE * STAGE : EPI_BYTES);
 };
 
-__device__ __forceinline__ u32x4 ldg16(const bf16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
+// Phi(h), the standard normal CDF, as 0.5 + h*Q(h^2) on |h| <= 4.2 (clamped beyond): degree-8 minimax
+// fit of Q, |error| < 1.2e-5 -- below the resolution of the bf16 values it is multiplied into -- and no
+// transcendental.  gelu(h) = h*Phi(h);  gelu'(h) = Phi(h) + h*phi(h).
+__device__ __forceinline__ float phi_cdf(float h, float& u) {
+    const float hc = __builtin_amdgcn_fmed3f(h, -4.2f, 4.2f);
+    u = hc * hc;
+    float q = 5.998071484e-11f;
+    q = fmaf(q, u, -5.633320033e-09f);
+    q = fmaf(q, u, 2.343674907e-07f);
+    q = fmaf(q, u, -5.760770819e-06f);
+    q = fmaf(q, u, 9.457441047e-05f);
+    q = fmaf(q, u, -1.114148065e-03f);
+    q = fmaf(q, u, 9.830130264e-03f);
+    q = fmaf(q, u, -6.636036932e-02f);
+    q = fmaf(q, u, 3.989074528e-01f);
+    return fmaf(hc, q, 0.5f);
+}
+__device__ __forceinline__ float act_fwd_fast(float h, int act) {
+    if (act == EVOMOE_RELU) return h > 0.f ? h : 0.f;
+    float u;
+    return h * phi_cdf(h, u);
+}
+__device__ __forceinline__ float act_grad_fast(float h, int act) {
+    if (act == EVOMOE_RELU) return h > 0.f ? 1.f : 0.f;
+    float u;
+    const float Phi = phi_cdf(h, u);
+    const float dens = 0.39894228040143267794f * __builtin_amdgcn_exp2f(u * -0.72134752044448170368f);
+    return fmaf(h, dens, Phi);         // beyond the clamp both terms are < 1e-3 of their limits
+}
 
-template <int LAYOUT, int EPI, int BM, int BN>
-__global__ __launch_bounds__(256) void grouped_gemm_bf16(GemmArgs p)
+// 16 bytes per lane, global -> LDS, no registers in between: lane l's data lands at lds + 16*l.
+__device__ __forceinline__ void load_to_lds(const bf16_t* gptr, unsigned char* lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
+                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+// s_waitcnt vmcnt(n) only (other counters left at their maxima)
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
+}
+
+template <int LAYOUT, int EPI, int BM, int BN, int BK, int NSTAGE, int WPE>
+__global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
 {
-    using G = Geo<LAYOUT, BM, BN>;
+    using G = Geo<LAYOUT, BM, BN, BK, NSTAGE>;
     constexpr int WM = G::WM, WN = G::WN;
     constexpr int TM = WM / 32, TN_ = WN / 32;               // MFMA tiles per wave
-    constexpr int A_LD = G::A_KC ? (BM * 8 / 256) : (64 * (BM / 8) / 256);   // 16-byte loads per thread per slab
-    constexpr int B_LD = G::B_KC ? (BN * 8 / 256) : (64 * (BN / 8) / 256);
+    constexpr int KS = BK / 16;                              // k-steps per slab
+    constexpr int A_LD = G::A_BYTES / 4096, B_LD = G::B_BYTES / 4096;   // 1 KB load instructions per wave per slab
+    constexpr int KC_CH = BK / 8, KC_RPI = 64 / KC_CH;       // k-contiguous: 16 B chunks per row, rows per instruction
+    constexpr int A_CPR = BM / 8, A_RPI = 64 / A_CPR;        // k-strided A: 16 B chunks per k-row, k-rows per instruction
+    constexpr int B_CPR = BN / 8, B_RPI = 64 / B_CPR;
+    constexpr int NMF = TM * TN_, NFR = TM + TN_, NLD = A_LD + B_LD;
+    static_assert(BK == 32 || BK == 64, "slab");
+    static_assert(WM % 32 == 0 && WN % 32 == 0 && A_LD >= 1 && B_LD >= 1 && NSTAGE >= 2 && KS % 2 == 0, "tile");
+    static_assert((NSTAGE - 2) * NLD <= 63, "vmcnt range");
 
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int offs[65];
@@ -86,7 +134,46 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(GemmArgs p)
     const int nct = (p.N + BN - 1) / BN;
     const int nmt = (LAYOUT == L_TN) ? (p.M + BM - 1) / BM : 1;
 
-    for (int tile = blockIdx.x;; tile += gridDim.x) {
+    // LDS byte offsets of this lane's operand fragments inside one stage (k-step 0), per MFMA tile
+    int fa_off[TM], fb_off[TN_];
+    const int s16 = lane & 15;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        if (G::A_KC) {
+            fa_off[i] = (wm * WM + i * 32 + l32) * (BK * 2);     // row base; the swizzled chunk is added per k-step
+        } else {
+            const int lb = (wm * WM + i * 32 + ((lane >> 4) & 1) * 16) >> 4;       // logical 32 B block
+            fa_off[i] = (kg * 8 + (s16 >> 2)) * (BM * 2) + ((lb ^ (s16 >> 2)) << 5) + ((s16 & 3) << 3);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < TN_; ++j) {
+        if (G::B_KC) {
+            fb_off[j] = (wn * WN + j * 32 + l32) * (BK * 2);
+        } else {
+            const int lb = (wn * WN + j * 32 + ((lane >> 4) & 1) * 16) >> 4;
+            fb_off[j] = (kg * 8 + (s16 >> 2)) * (BN * 2) + ((lb ^ (s16 >> 2)) << 5) + ((s16 & 3) << 3);
+        }
+    }
+    // swizzle key of this lane's fragment rows (tile rows start at multiples of 32)
+    const int sw = (BK == 64) ? (l32 & 7) : ((l32 >> 1) & 3);
+
+    // This lane's role in the 1 KB load instruction number (wave + 4*i) of a tile:
+    //   k-contiguous: row (wave+4i)*KC_RPI + lane/KC_CH, physical chunk lane%KC_CH -> logical chunk ^ key(row)
+    //   k-strided   : k-row (wave+4i)*RPI + lane/CPR, physical chunk lane%CPR -> logical chunk via block ^ (k & 3)
+    const int kc_row = lane / KC_CH;
+    const int kc_key = (BK == 64) ? (kc_row & 7) : ((kc_row >> 1) & 3);    // (wave+4i)*KC_RPI is a multiple of 8
+    const int kc_chunk = (lane % KC_CH) ^ kc_key;                           // logical 16 B chunk (8 k's)
+    const int ksA_row = lane / A_CPR, ksB_row = lane / B_CPR;
+    auto ks_col = [&](int pc, int krow) { return ((((pc >> 1) ^ (krow & 3)) << 1) | (pc & 1)) * 8; };
+
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber the blocks so that
+    // one XCD works on a run of consecutive tiles (which share A row panels and B column panels) and the
+    // operands are fetched into that L2 once instead of into all eight.
+    int vblock = blockIdx.x;
+    if ((gridDim.x & 7) == 0) vblock = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+
+    for (int tile = vblock;; tile += gridDim.x) {
         // ---------------- tile -> (expert, origin, contraction range) ----------------
         int g = 0, row0 = 0, rows = 0, n0 = 0, m0 = 0, kbeg = 0, kend = 0;
         if (LAYOUT == L_TN) {
@@ -119,89 +206,125 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(GemmArgs p)
             kend = p.K;
         }
         const int nslab = (kend - kbeg + BK - 1) / BK;
+        const bool ragged = (kend - kbeg) % BK != 0;     // block-uniform: the last slab is partial
+        const bf16_t* Bg = (LAYOUT == L_TN) ? p.B : p.B + (int64_t)g * p.b_group_stride;
 
-        // ---------------- per-thread global fetch plan ----------------
-        // k-contiguous tile: thread -> chunk tid%8 of rows tid/8 + 32*i
-        // k-strided tile  : thread -> chunk tid%(C/8) of k-rows tid/(C/8) + (256/(C/8))*i
+        // ---------------- per-lane global addresses of slab 0 ----------------
+        // Rows / columns outside the tile are clamped onto valid ones (their products are never stored);
+        // the tail of the contraction range is clamped too and then zeroed in LDS (A operand only).
         const bf16_t* a_ptr[A_LD];
-        bool a_ok[A_LD];
+        const bf16_t* b_ptr[B_LD];
+        int b_idx[B_LD];
         if (G::A_KC) {
 #pragma unroll
             for (int i = 0; i < A_LD; ++i) {
-                const int r = (tid >> 3) + 32 * i;
-                a_ok[i] = r < rows;
-                int64_t ar = 0;
-                if (a_ok[i]) ar = p.a_rows ? (int64_t)p.a_rows[row0 + r] : (int64_t)(row0 + r);
-                a_ptr[i] = p.A + ar * p.lda + (tid & 7) * 8;
+                const int r = min((wave + 4 * i) * KC_RPI + kc_row, rows - 1);
+                const int64_t ar = p.a_rows ? (int64_t)p.a_rows[row0 + r] : (int64_t)(row0 + r);
+                a_ptr[i] = p.A + ar * p.lda + kc_chunk * 8;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < A_LD; ++i) {
+                const int kr = (wave + 4 * i) * A_RPI + ksA_row;
+                const int m = min(m0 + ks_col(lane % A_CPR, kr), p.M - 8);
+                a_ptr[i] = p.A + (int64_t)(kbeg + kr) * p.lda + m;
             }
         }
-        const bf16_t* Bg = (LAYOUT == L_TN) ? p.B : p.B + (int64_t)g * p.b_group_stride;
-
-        u32x4 ra[A_LD], rb[B_LD];
-        const u32x4 zero4 = {0u, 0u, 0u, 0u};
-
-        auto fetch = [&](int slab) {
-            const int k0 = kbeg + slab * BK;
-            if (G::A_KC) {
+        if (G::B_KC) {
 #pragma unroll
-                for (int i = 0; i < A_LD; ++i) {
-                    const int k = k0 + (tid & 7) * 8;
-                    ra[i] = (a_ok[i] && k < kend) ? ldg16(a_ptr[i] + k0) : zero4;
-                }
-            } else {      // TN: L[r, m0 + ...]
-                constexpr int CPR = BM / 8, RPP = 256 / CPR;
-#pragma unroll
-                for (int i = 0; i < A_LD; ++i) {
-                    const int r = k0 + tid / CPR + RPP * i;
-                    const int m = m0 + (tid % CPR) * 8;
-                    ra[i] = (r < kend && m < p.M) ? ldg16(p.A + (int64_t)r * p.lda + m) : zero4;
-                }
+            for (int i = 0; i < B_LD; ++i) {
+                const int n = min(n0 + (wave + 4 * i) * KC_RPI + kc_row, p.N - 1);
+                b_ptr[i] = Bg + (int64_t)n * p.ldb + kc_chunk * 8;
             }
-            if (G::B_KC) {  // NT: W_g[n0 + row, k]
+        } else {
 #pragma unroll
-                for (int i = 0; i < B_LD; ++i) {
-                    const int n = n0 + (tid >> 3) + 32 * i;
-                    const int k = k0 + (tid & 7) * 8;
-                    rb[i] = (n < p.N && k < kend) ? ldg16(Bg + (int64_t)n * p.ldb + k) : zero4;
+            for (int i = 0; i < B_LD; ++i) {
+                const int kr = (wave + 4 * i) * B_RPI + ksB_row;
+                const int n = min(n0 + ks_col(lane % B_CPR, kr), p.N - 8);
+                b_ptr[i] = Bg + n + ((LAYOUT == L_TN && p.b_rows) ? 0 : (int64_t)(kbeg + kr) * p.ldb);
+            }
+        }
+        auto load_b_idx = [&](int slab) {       // TN with gathered R rows: row ids of one slab (clamped)
+            if (LAYOUT == L_TN && p.b_rows) {
+                const int k0 = kbeg + slab * BK;
+#pragma unroll
+                for (int i = 0; i < B_LD; ++i)
+                    b_idx[i] = p.b_rows[min(k0 + (wave + 4 * i) * B_RPI + ksB_row, kend - 1)];
+            }
+        };
+        // issue load instruction `idx` (A: 0..A_LD-1, then B) of slab `slab` into its stage; addresses
+        // are clamped into the contraction range (a no-op except in the last, partial slab)
+        auto issue_one = [&](int idx, int slab) {
+            unsigned char* sa = smem + (slab % NSTAGE) * G::STAGE + wave * 1024;
+            unsigned char* sb = sa + G::A_BYTES;
+            const int k0 = kbeg + slab * BK;            // absolute first k (row) of the slab
+            if (idx < A_LD) {
+                const int i = idx;
+                if (G::A_KC) {
+                    load_to_lds(a_ptr[i] + min(slab * BK, kend - 8 - kc_chunk * 8), sa + i * 4096);
+                } else {
+                    const int kr = (wave + 4 * i) * A_RPI + ksA_row;
+                    load_to_lds(a_ptr[i] + (int64_t)(min(k0 + kr, kend - 1) - (kbeg + kr)) * p.lda, sa + i * 4096);
                 }
             } else {
-                constexpr int CPR = BN / 8, RPP = 256 / CPR;
-#pragma unroll
-                for (int i = 0; i < B_LD; ++i) {
-                    const int r = k0 + tid / CPR + RPP * i;
-                    const int n = n0 + (tid % CPR) * 8;
-                    if (r < kend && n < p.N) {
-                        int64_t br = r;
-                        if (LAYOUT == L_TN && p.b_rows) br = p.b_rows[r];
-                        rb[i] = ldg16(Bg + br * p.ldb + n);
-                    } else {
-                        rb[i] = zero4;
-                    }
+                const int i = idx - A_LD;
+                if (G::B_KC) {
+                    load_to_lds(b_ptr[i] + min(slab * BK, kend - 8 - kc_chunk * 8), sb + i * 4096);
+                } else if (LAYOUT == L_TN && p.b_rows) {
+                    load_to_lds(b_ptr[i] + (int64_t)b_idx[i] * p.ldb, sb + i * 4096);
+                } else {
+                    const int kr = (wave + 4 * i) * B_RPI + ksB_row;
+                    load_to_lds(b_ptr[i] + (int64_t)(min(k0 + kr, kend - 1) - (kbeg + kr)) * p.ldb, sb + i * 4096);
                 }
             }
         };
-        auto stash = [&](int buf) {
-            unsigned char* sa = smem + buf * G::STAGE;
-            unsigned char* sb = sa + G::A_BYTES;
+        auto issue = [&](int slab) {
+#pragma unroll
+            for (int idx = 0; idx < NLD; ++idx) issue_one(idx, slab);
+        };
+        // zero the A operand beyond the end of the contraction range (last slab only)
+        auto zero_tail = [&](int slab) {
+            unsigned char* sa = smem + (slab % NSTAGE) * G::STAGE + wave * 1024;
+            const int k0 = kbeg + slab * BK;
+            const u32x4 z = {0u, 0u, 0u, 0u};
             if (G::A_KC) {
+                if (k0 + kc_chunk * 8 >= kend) {
 #pragma unroll
-                for (int i = 0; i < A_LD; ++i)
-                    *reinterpret_cast<u32x4*>(sa + kc_off((tid >> 3) + 32 * i, tid & 7)) = ra[i];
+                    for (int i = 0; i < A_LD; ++i) *reinterpret_cast<u32x4*>(sa + i * 4096 + lane * 16) = z;
+                }
             } else {
-                constexpr int CPR = BM / 8, RPP = 256 / CPR;
 #pragma unroll
                 for (int i = 0; i < A_LD; ++i)
-                    *reinterpret_cast<u32x4*>(sa + ks_off<BM>(tid / CPR + RPP * i, (tid % CPR) * 8)) = ra[i];
+                    if (k0 + (wave + 4 * i) * A_RPI + ksA_row >= kend)
+                        *reinterpret_cast<u32x4*>(sa + i * 4096 + lane * 16) = z;
             }
-            if (G::B_KC) {
-#pragma unroll
-                for (int i = 0; i < B_LD; ++i)
-                    *reinterpret_cast<u32x4*>(sb + kc_off((tid >> 3) + 32 * i, tid & 7)) = rb[i];
+        };
+        // operand fragment number f (A tiles 0..TM-1, then B tiles) of k-step ks of slab `slab`
+        auto read_frag = [&](int f, int slab, int ks, bf16x8* fa, bf16x8* fb) {
+            const unsigned char* sa = smem + (slab % NSTAGE) * G::STAGE;
+            const unsigned char* sb = sa + G::A_BYTES;
+            if (f < TM) {
+                const int i = f;
+                if (G::A_KC) {
+                    fa[i] = *reinterpret_cast<const bf16x8*>(sa + fa_off[i] + (((ks * 2 + kg) ^ sw) << 4));
+                } else {
+                    const unsigned char* q = sa + fa_off[i] + ks * 16 * (BM * 2);
+                    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(q));
+                    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(q + 4 * (BM * 2)));
+                    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    fa[i] = __builtin_bit_cast(bf16x8, v);
+                }
             } else {
-                constexpr int CPR = BN / 8, RPP = 256 / CPR;
-#pragma unroll
-                for (int i = 0; i < B_LD; ++i)
-                    *reinterpret_cast<u32x4*>(sb + ks_off<BN>(tid / CPR + RPP * i, (tid % CPR) * 8)) = rb[i];
+                const int j = f - TM;
+                if (G::B_KC) {
+                    fb[j] = *reinterpret_cast<const bf16x8*>(sb + fb_off[j] + (((ks * 2 + kg) ^ sw) << 4));
+                } else {
+                    const unsigned char* q = sb + fb_off[j] + ks * 16 * (BN * 2);
+                    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(q));
+                    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(q + 4 * (BN * 2)));
+                    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    fb[j] = __builtin_bit_cast(bf16x8, v);
+                }
             }
         };
 
@@ -213,88 +336,106 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(GemmArgs p)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-        __syncthreads();          // previous tile's epilogue has left the LDS
-        if (nslab > 0) {
-            fetch(0);
-            stash(0);
-        }
-        __syncthreads();
+        // One k-step: NMF MFMAs on fragments (FA, FB), in 8 groups; after each of the first four groups a
+        // share of the next k-step's fragment reads (into NA, NB; slab nslb, k-step nks) is issued, and
+        // after every group, optionally, a share of a later slab's global->LDS loads.  The scheduling
+        // fences pin this order.
+#define KSTEP(FA, FB, READ_NEXT, NA, NB, nslb, nks, LOADS, lslab)                                 \
+    _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                              \
+        _Pragma("unroll") for (int x = NMF * q / 8; x < NMF * (q + 1) / 8; ++x)                  \
+            acc[x / TN_][x % TN_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                     \
+                FA[x / TN_], FB[x % TN_], acc[x / TN_][x % TN_], 0, 0, 0);                       \
+        if (READ_NEXT && q < 4) {                                                                \
+            _Pragma("unroll") for (int f = NFR * q / 4; f < NFR * (q + 1) / 4; ++f)              \
+                read_frag(f, nslb, nks, NA, NB);                                                 \
+        }                                                                                        \
+        if (LOADS) {                                                                             \
+            _Pragma("unroll") for (int x = NLD * q / 8; x < NLD * (q + 1) / 8; ++x)              \
+                issue_one(x, lslab);                                                             \
+        }                                                                                        \
+        __builtin_amdgcn_sched_barrier(0);                                                       \
+    }
 
-        for (int slab = 0; slab < nslab; ++slab) {
-            const int buf = slab & 1;
-            if (slab + 1 < nslab) fetch(slab + 1);
-            const unsigned char* sa = smem + buf * G::STAGE;
-            const unsigned char* sb = sa + G::A_BYTES;
+        __syncthreads();          // previous tile's epilogue has left the LDS
+        bf16x8 fa0[TM], fb0[TN_], fa1[TM], fb1[TN_];
+        if (nslab > 0) {
+            // prologue: put NSTAGE-1 slabs in flight, wait for the first
+            load_b_idx(0);
 #pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
-                bf16x8 fa[TM], fb[TN_];
-#pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    if (G::A_KC) {
-                        const int row = wm * WM + i * 32 + l32;
-                        fa[i] = *reinterpret_cast<const bf16x8*>(sa + kc_off(row, ks * 2 + kg));
-                    } else {
-                        const int mb = wm * WM + i * 32 + ((lane >> 4) & 1) * 16 + 4 * (lane & 3);
-                        const int kb = ks * 16 + kg * 8 + ((lane & 15) >> 2);
-                        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (__attribute__((address_space(3))) s16x4*)(sa + ks_off<BM>(kb, mb)));
-                        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (__attribute__((address_space(3))) s16x4*)(sa + ks_off<BM>(kb + 4, mb)));
-                        s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        fa[i] = __builtin_bit_cast(bf16x8, v);
-                    }
+            for (int s = 0; s < NSTAGE - 1; ++s) {
+                if (s < nslab) {
+                    issue(s);
+                    load_b_idx(s + 1);
                 }
-#pragma unroll
-                for (int j = 0; j < TN_; ++j) {
-                    if (G::B_KC) {
-                        const int row = wn * WN + j * 32 + l32;
-                        fb[j] = *reinterpret_cast<const bf16x8*>(sb + kc_off(row, ks * 2 + kg));
-                    } else {
-                        const int nb = wn * WN + j * 32 + ((lane >> 4) & 1) * 16 + 4 * (lane & 3);
-                        const int kb = ks * 16 + kg * 8 + ((lane & 15) >> 2);
-                        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (__attribute__((address_space(3))) s16x4*)(sb + ks_off<BN>(kb, nb)));
-                        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (__attribute__((address_space(3))) s16x4*)(sb + ks_off<BN>(kb + 4, nb)));
-                        s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        fb[j] = __builtin_bit_cast(bf16x8, v);
-                    }
-                }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN_; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
             }
-            if (slab + 1 < nslab) stash(buf ^ 1);
+            if (nslab >= NSTAGE - 1) wait_vmcnt<(NSTAGE - 2) * NLD>(); else wait_vmcnt<0>();
             __syncthreads();
+            if (nslab == 1 && ragged) {
+                zero_tail(0);
+                __syncthreads();
+            }
+#pragma unroll
+            for (int f = 0; f < NFR; ++f) read_frag(f, 0, 0, fa0, fb0);
         }
+
+        // Slab s: k-steps 0..KS-1 on stage s % NSTAGE.  Fragments of the next k-step are read while the
+        // current one multiplies; loads of slab s+NSTAGE-1 go out under k-step 0 into the stage that slab
+        // s-1 has finished with; before the last k-step the block makes sure slab s+1 has landed.
+        auto slab_body = [&](int slab, auto loads_c) {
+            constexpr bool LOADS = decltype(loads_c)::value;
+            KSTEP(fa0, fb0, true, fa1, fb1, slab, 1, LOADS, slab + NSTAGE - 1);
+            if (LOADS) load_b_idx(slab + NSTAGE);
+            if (KS == 4) {
+                KSTEP(fa1, fb1, true, fa0, fb0, slab, 2, false, 0);
+                KSTEP(fa0, fb0, true, fa1, fb1, slab, 3, false, 0);
+            }
+            if (LOADS) wait_vmcnt<(NSTAGE - 2) * NLD>(); else wait_vmcnt<0>();
+            __syncthreads();
+            if (slab + 2 == nslab && ragged) {
+                zero_tail(slab + 1);
+                __syncthreads();
+            }
+            KSTEP(fa1, fb1, true, fa0, fb0, slab + 1, 0, false, 0);
+        };
+        int slab = 0;
+        for (; slab + NSTAGE - 1 < nslab; ++slab) slab_body(slab, std::true_type{});
+        for (; slab + 1 < nslab; ++slab) slab_body(slab, std::false_type{});
+        if (nslab > 0) {           // last slab: nothing left to fetch or to read ahead
+            KSTEP(fa0, fb0, true, fa1, fb1, slab, 1, false, 0);
+            if (KS == 4) {
+                KSTEP(fa1, fb1, true, fa0, fb0, slab, 2, false, 0);
+                KSTEP(fa0, fb0, true, fa1, fb1, slab, 3, false, 0);
+            }
+            KSTEP(fa1, fb1, false, fa0, fb0, 0, 0, false, 0);
+        }
+#undef KSTEP
+        __syncthreads();          // every wave is done reading operands: LDS becomes the epilogue's staging area
 
         // ---------------- epilogue: stage f32 rows through LDS, finish row-major ----------------
         // acc[i][j][r] is C(row = i*32 + 8*(r/4) + 4*kg + r%4, col = j*32 + l32) of the wave tile.
-        float* stg = reinterpret_cast<float*>(smem) + wave * (G::EPI_ROWS * G::EPI_LD);
+        constexpr int ER = G::EPI_ROWS;
+        float* stg = reinterpret_cast<float*>(smem) + wave * (ER * G::EPI_LD);
         constexpr int CPW = WN / 8;                 // 8-column chunks per wave-tile row
         constexpr int RPI = 64 / CPW;               // rows finished per instruction
 #pragma unroll
-        for (int half = 0; half < WM / 64; ++half) {
+        for (int pass = 0; pass < WM / ER; ++pass) {
 #pragma unroll
-            for (int ii = 0; ii < 2; ++ii) {
-                const int i = half * 2 + ii;
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN_; ++j)
+                for (int r = 0; r < 16; ++r) {
+                    const int wrow = i * 32 + 8 * (r >> 2);           // + 4*kg + (r&3) < 8
+                    if (wrow / ER != pass) continue;                  // compile-time after unrolling
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int row = ii * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
-                        stg[row * G::EPI_LD + j * 32 + l32] = acc[i][j][r];
-                    }
-            }
+                    for (int j = 0; j < TN_; ++j)
+                        stg[(wrow % ER + 4 * kg + (r & 3)) * G::EPI_LD + j * 32 + l32] = acc[i][j][r];
+                }
             __builtin_amdgcn_s_waitcnt(0xc07f);     // this wave's LDS writes are done (lgkmcnt(0))
             __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int it = 0; it < 64 / RPI; ++it) {
-                const int lr = it * RPI + lane / CPW;            // row inside the 64-row pass
+#pragma unroll 4
+            for (int it = 0; it < ER / RPI; ++it) {
+                const int lr = it * RPI + lane / CPW;            // row inside the pass
                 const int lc = (lane % CPW) * 8;                 // first of 8 columns
-                const int trow = wm * WM + half * 64 + lr;       // row inside the block tile
+                const int trow = wm * WM + pass * ER + lr;       // row inside the block tile
                 const int col = n0 + wn * WN + lc;
                 const f32x4 v0 = *reinterpret_cast<const f32x4*>(stg + lr * G::EPI_LD + lc);
                 const f32x4 v1 = *reinterpret_cast<const f32x4*>(stg + lr * G::EPI_LD + lc + 4);
@@ -326,13 +467,13 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(GemmArgs p)
                         float h[8];
                         Elem<bf16_t>::load_vec(p.Hin + grow * p.N + col, h);
 #pragma unroll
-                        for (int q = 0; q < 8; ++q) v[q] *= act_grad(h[q], p.act);
+                        for (int q = 0; q < 8; ++q) v[q] *= act_grad_fast(h[q], p.act);
                     }
                     Elem<bf16_t>::store_vec(p.out1 + grow * p.N + col, v);
                     if (EPI == E_HA) {
                         float a[8];
 #pragma unroll
-                        for (int q = 0; q < 8; ++q) a[q] = act_fwd(v[q], p.act);
+                        for (int q = 0; q < 8; ++q) a[q] = act_fwd_fast(v[q], p.act);
                         Elem<bf16_t>::store_vec(p.out2 + grow * p.N + col, a);
                     }
                 }
@@ -342,10 +483,16 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(GemmArgs p)
     }
 }
 
-template <int LAYOUT, int EPI, int BM, int BN>
+// Tile configurations.  BIG: one block per compute unit, 256 accumulator registers per lane.
+// DUO: two blocks per compute unit (one's epilogue and stalls hide under the other's MFMAs).
+struct CfgBig { static constexpr int BM = 256, BN = 256, BK = 64, NSTAGE = 2, WPE = 1; };
+struct CfgDuo { static constexpr int BM = 128, BN = 256, BK = 32, NSTAGE = 3, WPE = 2; };
+struct CfgBig4 { static constexpr int BM = 256, BN = 256, BK = 32, NSTAGE = 4, WPE = 1; };
+
+template <int LAYOUT, int EPI, class Cfg>
 hipError_t launch_gemm(const Ctx& c, const GemmArgs& a, int64_t worst_tiles) {
-    using G = Geo<LAYOUT, BM, BN>;
-    auto kern = grouped_gemm_bf16<LAYOUT, EPI, BM, BN>;
+    using G = Geo<LAYOUT, Cfg::BM, Cfg::BN, Cfg::BK, Cfg::NSTAGE>;
+    auto kern = grouped_gemm_bf16<LAYOUT, EPI, Cfg::BM, Cfg::BN, Cfg::BK, Cfg::NSTAGE, Cfg::WPE>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -353,36 +500,48 @@ hipError_t launch_gemm(const Ctx& c, const GemmArgs& a, int64_t worst_tiles) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    const int64_t cap = (int64_t)c.num_cu;
+    const int64_t cap = (int64_t)c.num_cu * Cfg::WPE;
     const int grid = (int)(worst_tiles < cap ? worst_tiles : cap);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), G::SMEM, c.stream, a);
     return hipGetLastError();
 }
+
+template <class Cfg> int64_t row_tiles(const evomoe_shape& s) { return (s.P_cap + Cfg::BM - 1) / Cfg::BM + s.E; }
+template <class Cfg> int64_t ctiles(int n) { return (n + Cfg::BN - 1) / Cfg::BN; }
+template <class Cfg> int64_t mtiles(int m) { return (m + Cfg::BM - 1) / Cfg::BM; }
+
+#ifndef EVOMOE_CFG_GEMM1
+#define EVOMOE_CFG_GEMM1 CfgDuo
+#define EVOMOE_CFG_GEMM2 CfgBig
+#define EVOMOE_CFG_DH CfgDuo
+#define EVOMOE_CFG_DX CfgBig
+#define EVOMOE_CFG_DW CfgBig
+#endif
 
 }  // namespace
 
 hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, const int32_t* pair_token,
                         const int32_t* expert_offsets, const void* W1, const float* b1, const void* W2,
                         const float* b2, void* H, void* A, void* O) {
-    constexpr int BM = 256, BN = 256;
-    const int64_t row_tiles = (s.P_cap + BM - 1) / BM + s.E;
     GemmArgs a{};
     a.expert_offsets = expert_offsets; a.E = s.E; a.P_cap = s.P_cap; a.act = s.act;
     hipError_t err;
     {   // H = X W1^T + b1, A = act(H)
+        using Cfg = EVOMOE_CFG_GEMM1;
         ProfScope ps(c, EVOMOE_K_FFN_GEMM1);
         a.A = (const bf16_t*)x; a.lda = s.d; a.a_rows = pair_token;
         a.B = (const bf16_t*)W1; a.ldb = s.d; a.b_group_stride = (int64_t)s.F * s.d;
         a.N = s.F; a.K = s.d; a.bias = b1; a.out1 = (bf16_t*)H; a.out2 = (bf16_t*)A;
-        err = launch_gemm<L_NT, E_HA, BM, BN>(c, a, row_tiles * ((s.F + BN - 1) / BN));
+        err = launch_gemm<L_NT, E_HA, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.F));
         if (err != hipSuccess) return err;
     }
     {   // O = A W2^T + b2
+        using Cfg = EVOMOE_CFG_GEMM2;
         ProfScope ps(c, EVOMOE_K_FFN_GEMM2);
         a.A = (const bf16_t*)A; a.lda = s.F; a.a_rows = nullptr;
         a.B = (const bf16_t*)W2; a.ldb = s.F; a.b_group_stride = (int64_t)s.d * s.F;
         a.N = s.d; a.K = s.F; a.bias = b2; a.out1 = (bf16_t*)O; a.out2 = nullptr;
-        err = launch_gemm<L_NT, E_BIAS, BM, BN>(c, a, row_tiles * ((s.d + BN - 1) / BN));
+        err = launch_gemm<L_NT, E_BIAS, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.d));
     }
     return err;
 }
@@ -391,48 +550,48 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
                         const void* x, const int32_t* pair_token, const int32_t* expert_offsets,
                         const void* W1, const void* W2, void* dW1, float* db1, void* dW2, float* db2,
                         void* dXp, int accumulate, void* dH) {
-    constexpr int BM = 256, BN = 256;
-    const int64_t row_tiles = (s.P_cap + BM - 1) / BM + s.E;
     GemmArgs a{};
     a.expert_offsets = expert_offsets; a.E = s.E; a.P_cap = s.P_cap; a.act = s.act;
     hipError_t err;
     {   // dH = (dO W2) * act'(H)
+        using Cfg = EVOMOE_CFG_DH;
         ProfScope ps(c, EVOMOE_K_FFN_BWD_DH);
         a.A = (const bf16_t*)dO; a.lda = s.d; a.B = (const bf16_t*)W2; a.ldb = s.F;
         a.b_group_stride = (int64_t)s.d * s.F; a.N = s.F; a.K = s.d; a.Hin = (const bf16_t*)H;
         a.out1 = (bf16_t*)dH;
-        err = launch_gemm<L_NN, E_ACTGRAD, BM, BN>(c, a, row_tiles * ((s.F + BN - 1) / BN));
+        err = launch_gemm<L_NN, E_ACTGRAD, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.F));
         if (err != hipSuccess) return err;
     }
     {   // dXp = dH W1
+        using Cfg = EVOMOE_CFG_DX;
         ProfScope ps(c, EVOMOE_K_FFN_BWD_DX);
         a.A = (const bf16_t*)dH; a.lda = s.F; a.B = (const bf16_t*)W1; a.ldb = s.d;
         a.b_group_stride = (int64_t)s.F * s.d; a.N = s.d; a.K = s.F; a.Hin = nullptr;
         a.out1 = (bf16_t*)dXp;
-        err = launch_gemm<L_NN, E_NONE, BM, BN>(c, a, row_tiles * ((s.d + BN - 1) / BN));
+        err = launch_gemm<L_NN, E_NONE, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.d));
         if (err != hipSuccess) return err;
     }
     a.accumulate = accumulate;
+    using CfgW = EVOMOE_CFG_DW;
     if (dW2) {   // dW2_g = dO_g^T A_g   [d,F]
         ProfScope ps(c, EVOMOE_K_FFN_BWD_DW2);
         a.A = (const bf16_t*)dO; a.lda = s.d; a.B = (const bf16_t*)A; a.ldb = s.F; a.b_rows = nullptr;
         a.M = s.d; a.N = s.F; a.out1 = (bf16_t*)dW2;
-        err = launch_gemm<L_TN, E_WGRAD, BM, BN>(
-            c, a, (int64_t)s.E * ((s.d + BM - 1) / BM) * ((s.F + BN - 1) / BN));
+        err = launch_gemm<L_TN, E_WGRAD, CfgW>(c, a, (int64_t)s.E * mtiles<CfgW>(s.d) * ctiles<CfgW>(s.F));
         if (err != hipSuccess) return err;
     }
     if (dW1) {   // dW1_g = dH_g^T X_g   [F,d]
         ProfScope ps(c, EVOMOE_K_FFN_BWD_DW1);
         a.A = (const bf16_t*)dH; a.lda = s.F; a.B = (const bf16_t*)x; a.ldb = s.d; a.b_rows = pair_token;
         a.M = s.F; a.N = s.d; a.out1 = (bf16_t*)dW1;
-        err = launch_gemm<L_TN, E_WGRAD, BM, BN>(
-            c, a, (int64_t)s.E * ((s.F + BM - 1) / BM) * ((s.d + BN - 1) / BN));
+        err = launch_gemm<L_TN, E_WGRAD, CfgW>(c, a, (int64_t)s.E * mtiles<CfgW>(s.F) * ctiles<CfgW>(s.d));
         if (err != hipSuccess) return err;
     }
     ProfScope ps(c, EVOMOE_K_FFN_BWD_DB);
-    if (db2) err = launch_colsum<bf16_t>(c, s, dO, s.d, expert_offsets, db2, accumulate);
+    float* scratch = reinterpret_cast<float*>(static_cast<char*>(dH) + dh_bytes(s));
+    if (db2) err = launch_colsum<bf16_t>(c, s, dO, s.d, expert_offsets, db2, accumulate, scratch);
     if (err != hipSuccess) return err;
-    if (db1) err = launch_colsum<bf16_t>(c, s, dH, s.F, expert_offsets, db1, accumulate);
+    if (db1) err = launch_colsum<bf16_t>(c, s, dH, s.F, expert_offsets, db1, accumulate, scratch);
     return err;
 }
 

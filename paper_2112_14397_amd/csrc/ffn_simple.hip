@@ -194,30 +194,81 @@ __global__ __launch_bounds__(256) void ffn_wgrad_kernel(
 
 }  // namespace
 
-// Bias gradient: db[g, n] = sum over the expert's rows of Mx[r, n]   (+ db if accumulate)
+// Bias gradient: db[g, n] = sum over the expert's rows of Mx[r, n]   (+ db if accumulate).
+// Pass 1: block = 64 columns (8 lanes x 16 bytes) x 32 row lanes, one of kColsumSplit row ranges of one
+// expert; f32 partial sums, tree-reduced over the row lanes in LDS, written to part[split][g][n].
+// Pass 2 adds the splits in order.  No atomics: the result is reproducible bit for bit.
+constexpr int kColsumSplit = 4;
+
 template <typename TX>
-__global__ __launch_bounds__(256) void ffn_colsum_kernel(
-    const TX* __restrict__ Mx, int N, const int32_t* __restrict__ expert_offsets, int64_t P_cap,
-    float* __restrict__ db, int accumulate)
+__global__ __launch_bounds__(256) void ffn_colsum_part_kernel(
+    const TX* __restrict__ Mx, int N, int E, const int32_t* __restrict__ expert_offsets, int64_t P_cap,
+    float* __restrict__ part)
 {
-    const int g = blockIdx.y, n = blockIdx.x * 256 + threadIdx.x;
-    if (n >= N) return;
+    constexpr int KV = Elem<TX>::kVec;           // elements per 16-byte load
+    constexpr int CL = 64 / KV;                  // column lanes covering 64 columns
+    constexpr int RL = 256 / CL;                 // row lanes
+    __shared__ float red[RL][64 + 1];
+    const int g = blockIdx.y, split = blockIdx.z;
+    const int cl = threadIdx.x % CL, rl = threadIdx.x / CL;
+    const int n = blockIdx.x * 64 + cl * KV;
     const int r0 = clamp_pairs(expert_offsets[g], P_cap), r1 = clamp_pairs(expert_offsets[g + 1], P_cap);
-    float s = 0.f;
-    for (int r = r0; r < r1; ++r) s += Elem<TX>::load(Mx + (size_t)r * N + n);
-    float* p = db + (size_t)g * N + n;
-    *p = accumulate ? *p + s : s;
+    const int per = (r1 - r0 + kColsumSplit - 1) / kColsumSplit;
+    const int rb = r0 + split * per, re = min(r1, rb + per);
+    float acc[KV];
+#pragma unroll
+    for (int q = 0; q < KV; ++q) acc[q] = 0.f;
+    if (n < N) {
+        for (int r = rb + rl; r < re; r += RL) {
+            float v[KV];
+            Elem<TX>::load_vec(Mx + (size_t)r * N + n, v);
+#pragma unroll
+            for (int q = 0; q < KV; ++q) acc[q] += v[q];
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < KV; ++q) red[rl][cl * KV + q] = acc[q];
+    __syncthreads();
+    for (int half = RL / 2; half > 0; half >>= 1) {
+        if (rl < half) {
+#pragma unroll
+            for (int q = 0; q < KV; ++q) red[rl][cl * KV + q] += red[rl + half][cl * KV + q];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x < 64) {
+        const int nn = blockIdx.x * 64 + threadIdx.x;
+        if (nn < N) part[((size_t)split * E + g) * N + nn] = red[0][threadIdx.x];
+    }
+}
+
+__global__ __launch_bounds__(256) void ffn_colsum_final_kernel(const float* __restrict__ part, size_t n,
+                                                               float* __restrict__ db, int accumulate)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float s = accumulate ? db[i] : 0.f;
+#pragma unroll
+    for (int k = 0; k < kColsumSplit; ++k) s += part[(size_t)k * n + i];
+    db[i] = s;
+}
+
+size_t colsum_scratch_bytes(const evomoe_shape& s) {
+    return (size_t)kColsumSplit * s.E * (s.d > s.F ? s.d : s.F) * sizeof(float);
 }
 
 template <typename TX>
 hipError_t launch_colsum(const Ctx& c, const evomoe_shape& s, const void* Mx, int N,
-                         const int32_t* expert_offsets, float* db, int accumulate) {
-    hipLaunchKernelGGL(ffn_colsum_kernel<TX>, dim3((N + 255) / 256, s.E), dim3(256), 0, c.stream,
-                       (const TX*)Mx, N, expert_offsets, s.P_cap, db, accumulate);
+                         const int32_t* expert_offsets, float* db, int accumulate, float* scratch) {
+    hipLaunchKernelGGL(ffn_colsum_part_kernel<TX>, dim3((N + 63) / 64, s.E, kColsumSplit), dim3(256), 0,
+                       c.stream, (const TX*)Mx, N, s.E, expert_offsets, s.P_cap, scratch);
+    const size_t n = (size_t)s.E * N;
+    hipLaunchKernelGGL(ffn_colsum_final_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, scratch, n,
+                       db, accumulate);
     return hipGetLastError();
 }
-template hipError_t launch_colsum<float>(const Ctx&, const evomoe_shape&, const void*, int, const int32_t*, float*, int);
-template hipError_t launch_colsum<bf16_t>(const Ctx&, const evomoe_shape&, const void*, int, const int32_t*, float*, int);
+template hipError_t launch_colsum<float>(const Ctx&, const evomoe_shape&, const void*, int, const int32_t*, float*, int, float*);
+template hipError_t launch_colsum<bf16_t>(const Ctx&, const evomoe_shape&, const void*, int, const int32_t*, float*, int, float*);
 
 static int row_tile_grid(const Ctx& c, const evomoe_shape& s) {
     const int64_t worst = (s.P_cap + BM - 1) / BM + s.E;
@@ -250,6 +301,7 @@ hipError_t simple_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, c
                           const int32_t* expert_offsets, const void* W1, const void* W2, void* dW1,
                           float* db1, void* dW2, float* db2, void* dXp, int accumulate, void* dH) {
     const int gx = row_tile_grid(c, s);
+    float* scratch = reinterpret_cast<float*>(static_cast<char*>(dH) + dh_bytes(s));
     // dH = (dO W2) * act'(H):  B_g(k, n) = W2[g][k][n]
     { ProfScope ps(c, EVOMOE_K_FFN_BWD_DH);
     hipLaunchKernelGGL((ffn_rows_kernel<TX, EPI_ACTGRAD>), dim3(gx, (s.F + BN - 1) / BN), dim3(256), 0,
@@ -277,9 +329,9 @@ hipError_t simple_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, c
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     ProfScope ps(c, EVOMOE_K_FFN_BWD_DB);
-    if (db2) err = launch_colsum<TX>(c, s, dO, s.d, expert_offsets, db2, accumulate);
+    if (db2) err = launch_colsum<TX>(c, s, dO, s.d, expert_offsets, db2, accumulate, scratch);
     if (err != hipSuccess) return err;
-    if (db1) err = launch_colsum<TX>(c, s, dH, s.F, expert_offsets, db1, accumulate);
+    if (db1) err = launch_colsum<TX>(c, s, dH, s.F, expert_offsets, db1, accumulate, scratch);
     return err;
 }
 
