@@ -64,7 +64,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--config", default="gpt")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-tokens", type=int, default=1024)
+    ap.add_argument("--cpu-tokens", type=int, default=3072)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="after the timed region, run a plain 512 MiB device-to-device copy three times "
+                         "(a kernel of known traffic, to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--profile-all", action="store_true",
                     help="also time every kernel with events in a second pass (adds 'kernels' to the JSON)")
     args = ap.parse_args()
@@ -164,6 +167,14 @@ def main():
         per_tau.append({"tau": round(tau, 3), "pairs": P_of[tau], "ms": ms, "tokens_per_s": cfg.T / ms * 1e3,
                         "tflops": 6.0 * flops_per_pair_gemm * P_of[tau] / ms / 1e9})
     out["per_tau"] = per_tau
+
+    if args.copy_probe:
+        src = torch.empty(512 * 1024 * 1024, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_probe_bytes"] = int(src.numel())
 
     if args.profile_all:
         B.evomoe_profile_select(ctx, "all")
