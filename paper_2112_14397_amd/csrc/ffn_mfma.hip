@@ -47,11 +47,13 @@ struct GemmArgs {
 // ---- LDS geometry -------------------------------------------------------------------------------
 // Operand tiles are written by direct global->LDS loads (64 lanes x 16 B land contiguously), so a stage
 // is a dense array and bank conflicts are avoided by permuting 16-byte chunks on the global side:
-//  * k-contiguous tile [R][BK k] bf16: chunk c of row r sits at chunk c ^ key(r), key = r & 7 (BK = 64,
-//    128-byte rows) or (r >> 1) & 3 (BK = 32, 64-byte rows): eight consecutive rows reading the same
-//    k-chunk with ds_read_b128 touch eight different bank groups;
-//  * k-strided tile [BK k][C cols] bf16, 2C B per row: 32-byte block b of row k sits at block b ^ (k & 3)
-//    (the transposing read ds_read_b64_tr_b16 takes the same block from four consecutive k rows).
+// (the LDS has 64 banks of 4 B: a ds_read_b128 is served 16 lanes = 256 B at a time, a 64-bit read 32 lanes)
+//  * k-contiguous tile [R][BK k] bf16: chunk c of row r sits at chunk c ^ key(r), key = (r >> 1) & 7
+//    (BK = 64, 128-byte rows) or (r >> 2) & 3 (BK = 32, 64-byte rows): sixteen consecutive rows reading
+//    the same k-chunk with ds_read_b128 cover all sixteen 16-byte slots of the 256-byte bank window;
+//  * k-strided tile [BK k][C cols] bf16, 2C B per row: 32-byte block b of row k sits at block
+//    b ^ 2(k & 3): the transposing read ds_read_b64_tr_b16 has 32 lanes take two adjacent blocks from
+//    four consecutive k rows, which then land in eight different 32-byte slots.
 template <int LAYOUT, int BM, int BN, int BK, int NSTAGE> struct Geo {
     static constexpr bool A_KC = (LAYOUT != L_TN);          // A operand k-contiguous?
     static constexpr bool B_KC = (LAYOUT == L_NT);
@@ -63,7 +65,8 @@ template <int LAYOUT, int BM, int BN, int BK, int NSTAGE> struct Geo {
     // rows of the wave tile staged per pass: as many as fit next to nothing else in the operand stages
     static constexpr int EPI_ROWS = (WM >= 64 && 4 * 64 * EPI_LD * 4 <= NSTAGE * STAGE + 8192) ? 64 : 32;
     static constexpr int EPI_BYTES = 4 * EPI_ROWS * EPI_LD * 4;
-    static constexpr int SMEM = (NSTAGE * STAGE > EPI_BYTES ? NSTAGE * STAGE : EPI_BYTES);
+    static constexpr int MAIN = (NSTAGE * STAGE > EPI_BYTES ? NSTAGE * STAGE : EPI_BYTES);
+    static constexpr int SMEM = MAIN + 1024;                 // + landing area of the L2 prefetch loads
 };
 
 // Phi(h), the standard normal CDF, as 0.5 + h*Q(h^2) on |h| <= 4.2 (clamped beyond): degree-8 minimax
@@ -97,13 +100,27 @@ __device__ __forceinline__ float act_grad_fast(float h, int act) {
 }
 
 // 16 bytes per lane, global -> LDS, no registers in between: lane l's data lands at lds + 16*l.
-__device__ __forceinline__ void load_to_lds(const bf16_t* gptr, unsigned char* lds_wave_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
-                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+// Written as inline assembly on purpose: the compiler cannot tell which LDS stage a load fills, so with
+// its own intrinsic it guards every later LDS read (and every barrier) with s_waitcnt vmcnt(0), which
+// serialises the prefetch pipeline.  Here the kernel counts its loads itself (wait_vmcnt below).
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+__device__ __forceinline__ void load_to_lds(const bf16_t* gptr, const unsigned char* lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(gptr), "s"(lds_addr(lds_wave_base)) : "m0", "memory");
+}
+__device__ __forceinline__ void touch_to_lds(const bf16_t* gptr, const unsigned char* lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :: "v"(gptr), "s"(lds_addr(lds_wave_base)) : "m0", "memory");
+}
+// Block barrier that orders LDS traffic only (global loads in flight stay in flight).
+__device__ __forceinline__ void block_sync_lds() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 // s_waitcnt vmcnt(n) only (other counters left at their maxima)
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
 template <int LAYOUT, int EPI, int BM, int BN, int BK, int NSTAGE, int WPE>
@@ -118,14 +135,21 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
     constexpr int A_CPR = BM / 8, A_RPI = 64 / A_CPR;        // k-strided A: 16 B chunks per k-row, k-rows per instruction
     constexpr int B_CPR = BN / 8, B_RPI = 64 / B_CPR;
     constexpr int NMF = TM * TN_, NFR = TM + TN_, NLD = A_LD + B_LD;
+    // L2 prefetch (one block per CU only): the streamed operand's lines of a slab PFD slabs beyond the one
+    // being loaded are touched with 4-byte loads, so that the 16-byte loads later hit in L2 instead of
+    // waiting for HBM with only NSTAGE-1 slabs of cover.
+    constexpr bool PF = (WPE == 1 && BK == 64 && BM == 256);
+    constexpr int PFD = 2;
+    constexpr int NPF = !PF ? 0 : (LAYOUT == L_TN ? 2 : 1);
     static_assert(BK == 32 || BK == 64, "slab");
     static_assert(WM % 32 == 0 && WN % 32 == 0 && A_LD >= 1 && B_LD >= 1 && NSTAGE >= 2 && KS % 2 == 0, "tile");
-    static_assert((NSTAGE - 2) * NLD <= 63, "vmcnt range");
+    static_assert((NSTAGE - 2) * NLD + (NSTAGE - 1) * 2 <= 63, "vmcnt range");
 
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int offs[65];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: lives in an SGPR
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, kg = lane >> 5;
     if (tid <= p.E) offs[tid] = clamp_pairs(p.expert_offsets[tid], p.P_cap);
@@ -143,7 +167,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
             fa_off[i] = (wm * WM + i * 32 + l32) * (BK * 2);     // row base; the swizzled chunk is added per k-step
         } else {
             const int lb = (wm * WM + i * 32 + ((lane >> 4) & 1) * 16) >> 4;       // logical 32 B block
-            fa_off[i] = (kg * 8 + (s16 >> 2)) * (BM * 2) + ((lb ^ (s16 >> 2)) << 5) + ((s16 & 3) << 3);
+            fa_off[i] = (kg * 8 + (s16 >> 2)) * (BM * 2) + ((lb ^ (2 * (s16 >> 2))) << 5) + ((s16 & 3) << 3);
         }
     }
 #pragma unroll
@@ -152,20 +176,21 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
             fb_off[j] = (wn * WN + j * 32 + l32) * (BK * 2);
         } else {
             const int lb = (wn * WN + j * 32 + ((lane >> 4) & 1) * 16) >> 4;
-            fb_off[j] = (kg * 8 + (s16 >> 2)) * (BN * 2) + ((lb ^ (s16 >> 2)) << 5) + ((s16 & 3) << 3);
+            fb_off[j] = (kg * 8 + (s16 >> 2)) * (BN * 2) + ((lb ^ (2 * (s16 >> 2))) << 5) + ((s16 & 3) << 3);
         }
     }
     // swizzle key of this lane's fragment rows (tile rows start at multiples of 32)
-    const int sw = (BK == 64) ? (l32 & 7) : ((l32 >> 1) & 3);
+    const int sw = (BK == 64) ? ((l32 >> 1) & 7) : ((l32 >> 2) & 3);
 
     // This lane's role in the 1 KB load instruction number (wave + 4*i) of a tile:
     //   k-contiguous: row (wave+4i)*KC_RPI + lane/KC_CH, physical chunk lane%KC_CH -> logical chunk ^ key(row)
     //   k-strided   : k-row (wave+4i)*RPI + lane/CPR, physical chunk lane%CPR -> logical chunk via block ^ (k & 3)
     const int kc_row = lane / KC_CH;
-    const int kc_key = (BK == 64) ? (kc_row & 7) : ((kc_row >> 1) & 3);    // (wave+4i)*KC_RPI is a multiple of 8
+    // key(row) of row (wave + 4i)*KC_RPI + kc_row does not depend on i
+    const int kc_key = (BK == 64) ? ((4 * (wave & 1) + (kc_row >> 1)) & 7) : ((kc_row >> 2) & 3);
     const int kc_chunk = (lane % KC_CH) ^ kc_key;                           // logical 16 B chunk (8 k's)
     const int ksA_row = lane / A_CPR, ksB_row = lane / B_CPR;
-    auto ks_col = [&](int pc, int krow) { return ((((pc >> 1) ^ (krow & 3)) << 1) | (pc & 1)) * 8; };
+    auto ks_col = [&](int pc, int krow) { return ((((pc >> 1) ^ (2 * (krow & 3))) << 1) | (pc & 1)) * 8; };
 
     // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber the blocks so that
     // one XCD works on a run of consecutive tiles (which share A row panels and B column panels) and the
@@ -244,6 +269,31 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
                 b_ptr[i] = Bg + n + ((LAYOUT == L_TN && p.b_rows) ? 0 : (int64_t)(kbeg + kr) * p.ldb);
             }
         }
+        // prefetch addresses: k-contiguous A: thread = tile row (one 128 B line per row and slab);
+        // k-strided (TN): thread = (k-row tid/4, 128 B segment tid%4) of the 64 x 512 B slab
+        const bf16_t* pf_a = p.A;
+        const bf16_t* pf_b = p.B;
+        if (PF) {
+            if (G::A_KC) {
+                const int r = min(tid, rows - 1);
+                pf_a = p.A + (p.a_rows ? (int64_t)p.a_rows[row0 + r] : (int64_t)(row0 + r)) * p.lda;
+            } else {
+                pf_a = p.A + min(m0 + (tid & 3) * 64, p.M - 8);
+                pf_b = p.B + min(n0 + (tid & 3) * 64, p.N - 8);
+            }
+        }
+        auto prefetch = [&](int slab) {
+            if (!PF) return;
+            unsigned char* sink = smem + G::MAIN + wave * 256;
+            const int sl = min(slab, nslab - 1);
+            if (G::A_KC) {
+                touch_to_lds(pf_a + min(sl * BK, kend - 8), sink);
+            } else {
+                const int64_t r = min(kbeg + sl * BK + (tid >> 2), kend - 1);
+                touch_to_lds(pf_a + r * p.lda, sink);
+                touch_to_lds(p.b_rows ? pf_a + r * p.lda : pf_b + r * p.ldb, sink);   // gathered rows: small, cache-resident
+            }
+        };
         auto load_b_idx = [&](int slab) {       // TN with gathered R rows: row ids of one slab (clamped)
             if (LAYOUT == L_TN && p.b_rows) {
                 const int k0 = kbeg + slab * BK;
@@ -356,7 +406,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
         __builtin_amdgcn_sched_barrier(0);                                                       \
     }
 
-        __syncthreads();          // previous tile's epilogue has left the LDS
+        __syncthreads();          // previous tile's epilogue has left the LDS (and its stores are on their way)
         bf16x8 fa0[TM], fb0[TN_], fa1[TM], fb1[TN_];
         if (nslab > 0) {
             // prologue: put NSTAGE-1 slabs in flight, wait for the first
@@ -368,11 +418,13 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
                     load_b_idx(s + 1);
                 }
             }
-            if (nslab >= NSTAGE - 1) wait_vmcnt<(NSTAGE - 2) * NLD>(); else wait_vmcnt<0>();
-            __syncthreads();
+#pragma unroll
+            for (int s = NSTAGE - 1; s < NSTAGE - 1 + PFD; ++s) prefetch(s);
+            if (nslab >= NSTAGE - 1 && NPF == 0) wait_vmcnt<(NSTAGE - 2) * NLD>(); else wait_vmcnt<0>();
+            block_sync_lds();
             if (nslab == 1 && ragged) {
                 zero_tail(0);
-                __syncthreads();
+                block_sync_lds();
             }
 #pragma unroll
             for (int f = 0; f < NFR; ++f) read_frag(f, 0, 0, fa0, fb0);
@@ -384,16 +436,18 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
         auto slab_body = [&](int slab, auto loads_c) {
             constexpr bool LOADS = decltype(loads_c)::value;
             KSTEP(fa0, fb0, true, fa1, fb1, slab, 1, LOADS, slab + NSTAGE - 1);
+            if (LOADS) prefetch(slab + NSTAGE - 1 + PFD);
             if (LOADS) load_b_idx(slab + NSTAGE);
             if (KS == 4) {
                 KSTEP(fa1, fb1, true, fa0, fb0, slab, 2, false, 0);
                 KSTEP(fa0, fb0, true, fa1, fb1, slab, 3, false, 0);
             }
-            if (LOADS) wait_vmcnt<(NSTAGE - 2) * NLD>(); else wait_vmcnt<0>();
-            __syncthreads();
+            // everything issued after slab+1's loads may still be in flight
+            if (LOADS) wait_vmcnt<(NSTAGE - 2) * NLD + (NSTAGE - 1) * NPF>(); else wait_vmcnt<0>();
+            block_sync_lds();
             if (slab + 2 == nslab && ragged) {
                 zero_tail(slab + 1);
-                __syncthreads();
+                block_sync_lds();
             }
             KSTEP(fa1, fb1, true, fa0, fb0, slab + 1, 0, false, 0);
         };
