@@ -30,8 +30,9 @@ PEAK_HBM_GBS = 8000.0
 
 
 def _gemm_kernels():
-    # expert-FFN GEMM kernels: each does 2*P*d*F flops per launch
-    return ("ffn_gemm1", "ffn_gemm2", "ffn_bwd_dh", "ffn_bwd_dx", "ffn_bwd_dw2", "ffn_bwd_dw1")
+    # expert-FFN GEMM launches and how many 2*P*d*F-flop contractions each carries
+    # (ffn_bwd_dw2 is the merged dW2 + dW1 launch; ffn_bwd_dw1 is only the gather of x feeding it)
+    return {"ffn_gemm1": 1, "ffn_gemm2": 1, "ffn_bwd_dh": 1, "ffn_bwd_dx": 1, "ffn_bwd_dw2": 2}
 
 
 def cpu_baseline(cfg, inp, n_tokens, taus):
@@ -187,7 +188,7 @@ def main():
         for name, (ms, n) in allp.items():
             ent = {"avg_us": ms * 1e3 / n, "launches": n}
             if name in _gemm_kernels():
-                ent["tflops"] = Psum * flops_per_pair_gemm / (ms * 1e-3) / 1e12
+                ent["tflops"] = _gemm_kernels()[name] * Psum * flops_per_pair_gemm / (ms * 1e-3) / 1e12
             ks[name] = ent
         out["kernels"] = ks
 

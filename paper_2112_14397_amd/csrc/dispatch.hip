@@ -41,15 +41,23 @@ __global__ __launch_bounds__(256) void dispatch_hist_kernel(
     __syncthreads();
     if (!is_last) return;
 
+    // ---- last block: turn the [nblk][E] histogram table into row bases, in chunks staged through LDS ----
     const int nblk = gridDim.x;
-    // column totals
-    if (tid < E) {
-        int sum = 0;
-        for (int b = 0; b < nblk; ++b)
-            sum += __hip_atomic_load(&block_counts[(size_t)b * E + tid], __ATOMIC_RELAXED,
-                                     __HIP_MEMORY_SCOPE_AGENT);
-        tot[tid + 1] = sum;
+    constexpr int kChunkInts = 8192;
+    __shared__ int tab[kChunkInts];
+    const int rows_per_chunk = min(kChunkInts / E, 256);      // one thread per block row in the scan
+    // pass A: column totals -> expert offsets
+    int mysum = 0;                                   // thread e < E accumulates column e
+    for (int b0 = 0; b0 < nblk; b0 += rows_per_chunk) {
+        const int nr = min(rows_per_chunk, nblk - b0);
+        for (int i = tid; i < nr * E; i += 256)
+            tab[i] = __hip_atomic_load(&block_counts[(size_t)b0 * E + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (tid < E)
+            for (int r = 0; r < nr; ++r) mysum += tab[r * E + tid];
+        __syncthreads();
     }
+    if (tid < E) tot[tid + 1] = mysum;
     if (tid == 0) tot[0] = 0;
     __syncthreads();
     if (tid == 0) {
@@ -62,22 +70,41 @@ __global__ __launch_bounds__(256) void dispatch_hist_kernel(
     }
     __syncthreads();
     if (tid <= E) expert_offsets[tid] = tot[tid];
-    // per-expert running base over blocks (thread e), per-block CSR base (one more pass)
-    if (tid < E) {
-        int run = tot[tid];
-        for (int b = 0; b < nblk; ++b) {
-            const size_t idx = (size_t)b * E + tid;
-            const int cur = __hip_atomic_load(&block_counts[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            block_counts[idx] = run;
-            run += cur;
+    // pass B: per-expert running base over blocks (thread e), and per-block CSR base (block scan)
+    int run = (tid < E) ? tot[tid] : 0;
+    int carry = 0;                                   // pairs owned by tokens of earlier chunks (uniform)
+    __shared__ int wsum[4];
+    for (int b0 = 0; b0 < nblk; b0 += rows_per_chunk) {
+        const int nr = min(rows_per_chunk, nblk - b0);
+        for (int i = tid; i < nr * E; i += 256)
+            tab[i] = __hip_atomic_load(&block_counts[(size_t)b0 * E + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        // pairs of block b0+tid, then an exclusive scan over the chunk's blocks
+        int mine = 0;
+        if (tid < nr)
+            for (int e = 0; e < E; ++e) mine += tab[tid * E + e];
+        int incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += v;
         }
-    }
-    __syncthreads();
-    // tok_base[b] = pairs owned by tokens of blocks < b  = sum_e (base[b][e] - offsets[e])
-    for (int b = tid; b < nblk; b += 256) {
-        int sum = 0;
-        for (int e = 0; e < E; ++e) sum += block_counts[(size_t)b * E + e] - tot[e];
-        tok_base[b] = sum;
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        int before = carry;
+        for (int w = 0; w < wave; ++w) before += wsum[w];
+        if (tid < nr) tok_base[b0 + tid] = before + incl - mine;
+        carry += wsum[0] + wsum[1] + wsum[2] + wsum[3];
+        if (tid < E) {
+            for (int r = 0; r < nr; ++r) {
+                const int cur = tab[r * E + tid];
+                tab[r * E + tid] = run;
+                run += cur;
+            }
+        }
+        __syncthreads();
+        for (int i = tid; i < nr * E; i += 256) block_counts[(size_t)b0 * E + i] = tab[i];
+        __syncthreads();
     }
 }
 
@@ -144,6 +171,15 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(
     }
 }
 
+hipError_t launch_gather_rows(const Ctx& c, const evomoe_shape& s, const void* x, const int32_t* pair_token,
+                              const int32_t* expert_offsets, void* x_perm) {
+    const int esz = s.dtype == EVOMOE_BF16 ? 2 : 4;
+    const int vec_per_row = s.d * esz / 16;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(c.num_cu * 8), dim3(256), 0, c.stream, (const u32x4*)x,
+                       pair_token, expert_offsets, s.E, s.P_cap, vec_per_row, (u32x4*)x_perm);
+    return hipGetLastError();
+}
+
 hipError_t launch_dispatch(const Ctx& c, const evomoe_shape& s, const uint64_t* mask_bits,
                            const float* scores, int32_t* expert_offsets, int32_t* pair_token,
                            float* pair_gate, int32_t* tok_off, int32_t* tok_rows, int64_t* num_pairs,
@@ -162,13 +198,7 @@ hipError_t launch_dispatch(const Ctx& c, const evomoe_shape& s, const uint64_t* 
         hipLaunchKernelGGL(dispatch_scatter_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, scores,
                            s.T, s.E, s.P_cap, base, tok_base, pair_token, pair_gate, tok_off, tok_rows);
     }
-    if (x_perm) {
-        const int esz = s.dtype == EVOMOE_BF16 ? 2 : 4;
-        const int vec_per_row = s.d * esz / 16;
-        hipLaunchKernelGGL(gather_rows_kernel, dim3(c.num_cu * 8), dim3(256), 0, c.stream,
-                           (const u32x4*)x, pair_token, expert_offsets, s.E, s.P_cap, vec_per_row,
-                           (u32x4*)x_perm);
-    }
+    if (x_perm) return launch_gather_rows(c, s, x, pair_token, expert_offsets, x_perm);
     return hipGetLastError();
 }
 

@@ -4,7 +4,9 @@
 namespace evomoe {
 
 size_t ffn_bwd_workspace_bytes(const evomoe_shape& s) {
-    return dh_bytes(s) + colsum_scratch_bytes(s);
+    // [dH][bias-gradient partials][gathered copy of x for the dW1 GEMM (bf16 layer)]
+    const size_t xp = s.dtype == EVOMOE_BF16 ? (size_t)s.P_cap * s.d * 2 : 0;
+    return dh_bytes(s) + colsum_scratch_bytes(s) + xp;
 }
 
 hipError_t launch_expert_ffn(const Ctx& c, const evomoe_shape& s, const void* x,

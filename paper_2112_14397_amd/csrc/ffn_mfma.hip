@@ -32,7 +32,6 @@ struct GemmArgs {
     const bf16_t* B;  int64_t ldb;      // NT: W_g [N,K] (ldb = K);  NN: W_g [K,N] (ldb = N);  TN: R [*,N] (ldb = N)
     int64_t b_group_stride;             // NT/NN: elements between two experts' weight matrices
     const int32_t* a_rows;              // NT: gather of A rows (or null)
-    const int32_t* b_rows;              // TN: gather of R rows (or null)
     const int32_t* expert_offsets;
     int E;
     int64_t P_cap;
@@ -124,8 +123,10 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 }
 
 template <int LAYOUT, int EPI, int BM, int BN, int BK, int NSTAGE, int WPE>
-__global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
+__global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmArgs q1, int tiles0)
 {
+    // TN launches carry two independent problems (dW2 and dW1) in one grid, tiles [0, tiles0) and
+    // [tiles0, ...), which evens out the last round of the persistent schedule; other layouts use q0 only.
     using G = Geo<LAYOUT, BM, BN, BK, NSTAGE>;
     constexpr int WM = G::WM, WN = G::WN;
     constexpr int TM = WM / 32, TN_ = WN / 32;               // MFMA tiles per wave
@@ -152,11 +153,8 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: lives in an SGPR
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, kg = lane >> 5;
-    if (tid <= p.E) offs[tid] = clamp_pairs(p.expert_offsets[tid], p.P_cap);
+    if (tid <= q0.E) offs[tid] = clamp_pairs(q0.expert_offsets[tid], q0.P_cap);
     __syncthreads();
-
-    const int nct = (p.N + BN - 1) / BN;
-    const int nmt = (LAYOUT == L_TN) ? (p.M + BM - 1) / BM : 1;
 
     // LDS byte offsets of this lane's operand fragments inside one stage (k-step 0), per MFMA tile
     int fa_off[TM], fb_off[TN_];
@@ -198,8 +196,13 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
     int vblock = blockIdx.x;
     if ((gridDim.x & 7) == 0) vblock = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
 
-    for (int tile = vblock;; tile += gridDim.x) {
-        // ---------------- tile -> (expert, origin, contraction range) ----------------
+    for (int vtile = vblock;; vtile += gridDim.x) {
+        // ---------------- tile -> (problem, expert, origin, contraction range) ----------------
+        const bool second = (LAYOUT == L_TN) && vtile >= tiles0;
+        const GemmArgs& p = second ? q1 : q0;
+        const int tile = second ? vtile - tiles0 : vtile;
+        const int nct = (p.N + BN - 1) / BN;
+        const int nmt = (LAYOUT == L_TN) ? (p.M + BM - 1) / BM : 1;
         int g = 0, row0 = 0, rows = 0, n0 = 0, m0 = 0, kbeg = 0, kend = 0;
         if (LAYOUT == L_TN) {
             if (tile >= p.E * nmt * nct) break;
@@ -239,7 +242,6 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
         // the tail of the contraction range is clamped too and then zeroed in LDS (A operand only).
         const bf16_t* a_ptr[A_LD];
         const bf16_t* b_ptr[B_LD];
-        int b_idx[B_LD];
         if (G::A_KC) {
 #pragma unroll
             for (int i = 0; i < A_LD; ++i) {
@@ -266,7 +268,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
             for (int i = 0; i < B_LD; ++i) {
                 const int kr = (wave + 4 * i) * B_RPI + ksB_row;
                 const int n = min(n0 + ks_col(lane % B_CPR, kr), p.N - 8);
-                b_ptr[i] = Bg + n + ((LAYOUT == L_TN && p.b_rows) ? 0 : (int64_t)(kbeg + kr) * p.ldb);
+                b_ptr[i] = Bg + n + (int64_t)(kbeg + kr) * p.ldb;
             }
         }
         // prefetch addresses: k-contiguous A: thread = tile row (one 128 B line per row and slab);
@@ -291,15 +293,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
             } else {
                 const int64_t r = min(kbeg + sl * BK + (tid >> 2), kend - 1);
                 touch_to_lds(pf_a + r * p.lda, sink);
-                touch_to_lds(p.b_rows ? pf_a + r * p.lda : pf_b + r * p.ldb, sink);   // gathered rows: small, cache-resident
-            }
-        };
-        auto load_b_idx = [&](int slab) {       // TN with gathered R rows: row ids of one slab (clamped)
-            if (LAYOUT == L_TN && p.b_rows) {
-                const int k0 = kbeg + slab * BK;
-#pragma unroll
-                for (int i = 0; i < B_LD; ++i)
-                    b_idx[i] = p.b_rows[min(k0 + (wave + 4 * i) * B_RPI + ksB_row, kend - 1)];
+                touch_to_lds(pf_b + r * p.ldb, sink);
             }
         };
         // issue load instruction `idx` (A: 0..A_LD-1, then B) of slab `slab` into its stage; addresses
@@ -320,8 +314,6 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
                 const int i = idx - A_LD;
                 if (G::B_KC) {
                     load_to_lds(b_ptr[i] + min(slab * BK, kend - 8 - kc_chunk * 8), sb + i * 4096);
-                } else if (LAYOUT == L_TN && p.b_rows) {
-                    load_to_lds(b_ptr[i] + (int64_t)b_idx[i] * p.ldb, sb + i * 4096);
                 } else {
                     const int kr = (wave + 4 * i) * B_RPI + ksB_row;
                     load_to_lds(b_ptr[i] + (int64_t)(min(k0 + kr, kend - 1) - (kbeg + kr)) * p.ldb, sb + i * 4096);
@@ -410,13 +402,9 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
         bf16x8 fa0[TM], fb0[TN_], fa1[TM], fb1[TN_];
         if (nslab > 0) {
             // prologue: put NSTAGE-1 slabs in flight, wait for the first
-            load_b_idx(0);
 #pragma unroll
             for (int s = 0; s < NSTAGE - 1; ++s) {
-                if (s < nslab) {
-                    issue(s);
-                    load_b_idx(s + 1);
-                }
+                if (s < nslab) issue(s);
             }
 #pragma unroll
             for (int s = NSTAGE - 1; s < NSTAGE - 1 + PFD; ++s) prefetch(s);
@@ -437,7 +425,6 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs p)
             constexpr bool LOADS = decltype(loads_c)::value;
             KSTEP(fa0, fb0, true, fa1, fb1, slab, 1, LOADS, slab + NSTAGE - 1);
             if (LOADS) prefetch(slab + NSTAGE - 1 + PFD);
-            if (LOADS) load_b_idx(slab + NSTAGE);
             if (KS == 4) {
                 KSTEP(fa1, fb1, true, fa0, fb0, slab, 2, false, 0);
                 KSTEP(fa0, fb0, true, fa1, fb1, slab, 3, false, 0);
@@ -544,7 +531,7 @@ struct CfgDuo { static constexpr int BM = 128, BN = 256, BK = 32, NSTAGE = 3, WP
 struct CfgBig4 { static constexpr int BM = 256, BN = 256, BK = 32, NSTAGE = 4, WPE = 1; };
 
 template <int LAYOUT, int EPI, class Cfg>
-hipError_t launch_gemm(const Ctx& c, const GemmArgs& a, int64_t worst_tiles) {
+hipError_t launch_gemm(const Ctx& c, const GemmArgs& a0, int64_t tiles0, const GemmArgs& a1, int64_t tiles1) {
     using G = Geo<LAYOUT, Cfg::BM, Cfg::BN, Cfg::BK, Cfg::NSTAGE>;
     auto kern = grouped_gemm_bf16<LAYOUT, EPI, Cfg::BM, Cfg::BN, Cfg::BK, Cfg::NSTAGE, Cfg::WPE>;
     static bool configured = false;
@@ -554,10 +541,14 @@ hipError_t launch_gemm(const Ctx& c, const GemmArgs& a, int64_t worst_tiles) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    const int64_t cap = (int64_t)c.num_cu * Cfg::WPE;
-    const int grid = (int)(worst_tiles < cap ? worst_tiles : cap);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), G::SMEM, c.stream, a);
+    const int64_t cap = (int64_t)c.num_cu * Cfg::WPE, worst = tiles0 + tiles1;
+    const int grid = (int)(worst < cap ? worst : cap);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), G::SMEM, c.stream, a0, a1, (int)tiles0);
     return hipGetLastError();
+}
+template <int LAYOUT, int EPI, class Cfg>
+hipError_t launch_gemm(const Ctx& c, const GemmArgs& a, int64_t worst_tiles) {
+    return launch_gemm<LAYOUT, EPI, Cfg>(c, a, worst_tiles, a, 0);
 }
 
 template <class Cfg> int64_t row_tiles(const evomoe_shape& s) { return (s.P_cap + Cfg::BM - 1) / Cfg::BM + s.E; }
@@ -627,20 +618,35 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
     }
     a.accumulate = accumulate;
     using CfgW = EVOMOE_CFG_DW;
-    if (dW2) {   // dW2_g = dO_g^T A_g   [d,F]
-        ProfScope ps(c, EVOMOE_K_FFN_BWD_DW2);
-        a.A = (const bf16_t*)dO; a.lda = s.d; a.B = (const bf16_t*)A; a.ldb = s.F; a.b_rows = nullptr;
-        a.M = s.d; a.N = s.F; a.out1 = (bf16_t*)dW2;
-        err = launch_gemm<L_TN, E_WGRAD, CfgW>(c, a, (int64_t)s.E * mtiles<CfgW>(s.d) * ctiles<CfgW>(s.F));
-        if (err != hipSuccess) return err;
-    }
-    if (dW1) {   // dW1_g = dH_g^T X_g   [F,d]
+    GemmArgs w2 = a, w1 = a;
+    // dW2_g = dO_g^T A_g   [d,F]
+    w2.A = (const bf16_t*)dO; w2.lda = s.d; w2.B = (const bf16_t*)A; w2.ldb = s.F;
+    w2.M = s.d; w2.N = s.F; w2.out1 = (bf16_t*)dW2;
+    const int64_t t2 = (int64_t)s.E * mtiles<CfgW>(s.d) * ctiles<CfgW>(s.F);
+    // dW1_g = dH_g^T X_g   [F,d]; the token rows are gathered once into a dense copy so that the GEMM
+    // streams them like any other operand
+    const bf16_t* xg = (const bf16_t*)x;
+    if (dW1 && pair_token) {
         ProfScope ps(c, EVOMOE_K_FFN_BWD_DW1);
-        a.A = (const bf16_t*)dH; a.lda = s.F; a.B = (const bf16_t*)x; a.ldb = s.d; a.b_rows = pair_token;
-        a.M = s.F; a.N = s.d; a.out1 = (bf16_t*)dW1;
-        err = launch_gemm<L_TN, E_WGRAD, CfgW>(c, a, (int64_t)s.E * mtiles<CfgW>(s.F) * ctiles<CfgW>(s.d));
+        bf16_t* xp = reinterpret_cast<bf16_t*>(static_cast<char*>(dH) + dh_bytes(s) + colsum_scratch_bytes(s));
+        err = launch_gather_rows(c, s, x, pair_token, expert_offsets, xp);
         if (err != hipSuccess) return err;
+        xg = xp;
     }
+    w1.A = (const bf16_t*)dH; w1.lda = s.F; w1.B = xg; w1.ldb = s.d;
+    w1.M = s.F; w1.N = s.d; w1.out1 = (bf16_t*)dW1;
+    const int64_t t1 = (int64_t)s.E * mtiles<CfgW>(s.F) * ctiles<CfgW>(s.d);
+    if (dW2 && dW1) {
+        ProfScope ps(c, EVOMOE_K_FFN_BWD_DW2);
+        err = launch_gemm<L_TN, E_WGRAD, CfgW>(c, w2, t2, w1, t1);
+    } else if (dW2) {
+        ProfScope ps(c, EVOMOE_K_FFN_BWD_DW2);
+        err = launch_gemm<L_TN, E_WGRAD, CfgW>(c, w2, t2);
+    } else if (dW1) {
+        ProfScope ps(c, EVOMOE_K_FFN_BWD_DW1);
+        err = launch_gemm<L_TN, E_WGRAD, CfgW>(c, w1, t1);
+    }
+    if (err != hipSuccess) return err;
     ProfScope ps(c, EVOMOE_K_FFN_BWD_DB);
     float* scratch = reinterpret_cast<float*>(static_cast<char*>(dH) + dh_bytes(s));
     if (db2) err = launch_colsum<bf16_t>(c, s, dO, s.d, expert_offsets, db2, accumulate, scratch);

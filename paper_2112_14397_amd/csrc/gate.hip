@@ -32,7 +32,6 @@ __global__ __launch_bounds__(256) void dts_gate_kernel(
 
     __shared__ float zsum[TPB * LDZ];
     __shared__ int cnt[64];
-    __shared__ int part[4][64];
     __shared__ int is_last;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -172,15 +171,25 @@ __global__ __launch_bounds__(256) void dts_gate_kernel(
     }
     __syncthreads();
     if (is_last) {
-        const int e = tid & 63, p = tid >> 6;
-        int sum = 0;
-        if (e < E)
-            for (int b = p; b < (int)gridDim.x; b += 4)
-                sum += __hip_atomic_load(&block_counts[(size_t)b * E + e], __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
-        part[p][e] = sum;
+        // all 256 threads stream the [blocks][E] table (independent, coalesced loads) into LDS counters
+        if (tid < 64) cnt[tid] = 0;
         __syncthreads();
-        if (tid < E) counts[tid] = part[0][tid] + part[1][tid] + part[2][tid] + part[3][tid];
+        const int total = (int)gridDim.x * E;
+        for (int base = 0; base < total; base += 256 * 8) {
+            int v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256 + tid;
+                v[u] = idx < total ? __hip_atomic_load(&block_counts[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256 + tid;
+                if (idx < total && v[u]) atomicAdd(&cnt[idx % E], v[u]);
+            }
+        }
+        __syncthreads();
+        if (tid < E) counts[tid] = cnt[tid];
         if (tid == 0) atomicExch(ticket, 0);     // ready for the next launch on this stream
     }
 }
@@ -313,19 +322,32 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(
         w[e] = (e < E) ? Wg[(size_t)k * E + e] : 0.f;
         g[e] = 0.f;
     }
-    for (int s = 0; s < ns; ++s) {
-        const size_t off = (size_t)(s0 + s) * d + k;
-        const float xv = Elem<TX>::load(x + off);
-        float acc = 0.f;
+    // tokens in groups of 8: the group's loads of x and dx are issued together, then used
+    for (int sb = 0; sb < ns; sb += 8) {
+        float xv[8], dxv[8];
 #pragma unroll
-        for (int e = 0; e < EP; ++e) {
-            if (e < E) {
-                const float z = sdz[s * E + e];
-                acc += z * w[e];
-                g[e] += xv * z;
+        for (int u = 0; u < 8; ++u) {
+            const int s = min(sb + u, ns - 1);
+            const size_t off = (size_t)(s0 + s) * d + k;
+            xv[u] = Elem<TX>::load(x + off);
+            dxv[u] = Elem<TX>::load(dx + off);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int s = sb + u;
+            if (s < ns) {
+                float acc = 0.f;
+#pragma unroll
+                for (int e = 0; e < EP; ++e) {
+                    if (e < E) {
+                        const float z = sdz[s * E + e];
+                        acc += z * w[e];
+                        g[e] += xv[u] * z;
+                    }
+                }
+                Elem<TX>::store(dx + (size_t)(s0 + s) * d + k, dxv[u] + acc);
             }
         }
-        Elem<TX>::store(dx + off, Elem<TX>::load(dx + off) + acc);
     }
 #pragma unroll
     for (int e = 0; e < EP; ++e)
@@ -339,7 +361,13 @@ __global__ __launch_bounds__(256) void sum_chunks_kernel(const float* __restrict
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
     float s = 0.f;
-    for (int c = 0; c < nchunk; ++c) s += part[(size_t)c * n + i];
+    for (int c0 = 0; c0 < nchunk; c0 += 16) {      // 16 independent loads in flight, added in chunk order
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = (c0 + u < nchunk) ? part[(size_t)(c0 + u) * n + i] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) s += v[u];
+    }
     out[i] = s;
 }
 

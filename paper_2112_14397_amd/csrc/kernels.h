@@ -22,6 +22,8 @@ hipError_t launch_dispatch(const Ctx& c, const evomoe_shape& s, const uint64_t* 
                            float* pair_gate, int32_t* tok_off, int32_t* tok_rows, int64_t* num_pairs,
                            const void* x, void* x_perm);
 int dispatch_blocks(const evomoe_shape& s);
+hipError_t launch_gather_rows(const Ctx& c, const evomoe_shape& s, const void* x, const int32_t* pair_token,
+                              const int32_t* expert_offsets, void* x_perm);   // x_perm[r,:] = x[pair_token[r],:]
 hipError_t launch_dispatch_bwd(const Ctx& c, const evomoe_shape& s, const void* dXp,
                                const int32_t* tok_off, const int32_t* tok_rows, void* dx);
 
