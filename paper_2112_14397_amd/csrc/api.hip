@@ -53,6 +53,21 @@ evomoe_status ensure_scratch(Ctx& c, size_t elems) {
     return EVOMOE_OK;
 }
 
+// Scratch of the bf16 gate (split copy of W_g); grows with a device allocation when a larger d*E shows up.
+evomoe_status ensure_wg_planes(Ctx& c, size_t bytes) {
+    if (bytes <= c.wg_planes_bytes) return EVOMOE_OK;
+    if (c.wg_planes) {
+        if (hipStreamSynchronize(c.stream) != hipSuccess) return EVOMOE_EHIP;
+        if (hipFree(c.wg_planes) != hipSuccess) return EVOMOE_EHIP;
+        c.wg_planes = nullptr;
+        c.wg_planes_bytes = 0;
+    }
+    const size_t want = bytes < (1u << 20) ? (1u << 20) : bytes;
+    if (hipMalloc(&c.wg_planes, want) != hipSuccess) return EVOMOE_EHIP;
+    c.wg_planes_bytes = want;
+    return EVOMOE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -66,6 +81,8 @@ evomoe_status evomoe_create(evomoe_ctx** ctx_out, void* hip_stream) {
     c.stream = (hipStream_t)hip_stream;
     c.block_counts = nullptr;
     c.block_counts_elems = 0;
+    c.wg_planes = nullptr;
+    c.wg_planes_bytes = 0;
     c.status_dev = nullptr;
     c.prof = nullptr;
     hipDeviceProp_t prop;
@@ -92,6 +109,7 @@ evomoe_status evomoe_destroy(evomoe_ctx* ctx) {
     if (!ctx) return EVOMOE_EINVAL;
     (void)hipStreamSynchronize(ctx->c.stream);
     if (ctx->c.block_counts) (void)hipFree(ctx->c.block_counts);
+    if (ctx->c.wg_planes) (void)hipFree(ctx->c.wg_planes);
     if (ctx->c.status_dev) (void)hipFree(ctx->c.status_dev);
     if (ctx->c.prof) {
         for (int i = 0; i < ctx->c.prof->cap; ++i) {
@@ -134,6 +152,10 @@ evomoe_status evomoe_dts_gate(evomoe_ctx* ctx, const evomoe_shape* shape, const 
     if (!(tau > 0.f) || !(threshold >= 0.f)) return EVOMOE_EINVAL;
     evomoe_status st = ensure_scratch(ctx->c, (size_t)gate_blocks(ctx->c, *shape) * shape->E);
     if (st != EVOMOE_OK) return st;
+    if (shape->dtype == EVOMOE_BF16) {
+        st = ensure_wg_planes(ctx->c, (size_t)3 * 64 * shape->d * sizeof(uint16_t));
+        if (st != EVOMOE_OK) return st;
+    }
     return from_hip(launch_dts_gate(ctx->c, *shape, x, Wg, bg, noise, tau, threshold, gprime, gate_w,
                                     mask_bits, counts, k_per_token));
 }

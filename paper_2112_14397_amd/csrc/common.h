@@ -109,6 +109,8 @@ struct Ctx {
     int32_t* ticket_dev;      // [1] arrival counter of the gate's last-block reduction
     int32_t* block_counts;    // scratch for per-block expert histograms
     size_t block_counts_elems;
+    uint16_t* wg_planes;      // bf16 gate: W_g split into three bf16 terms, transposed ([3][16*NE][d])
+    size_t wg_planes_bytes;
     Prof* prof;
 };
 

@@ -8,19 +8,11 @@ namespace evomoe {
 
 int dispatch_blocks(const evomoe_shape& s) { return (s.T + kDispatchTokens - 1) / kDispatchTokens; }
 
-// Pass 1: per-block (256 consecutive tokens) expert histogram.  The last block to finish turns the
-// table into  base[b][e] = first row of expert e's tokens that live in block b,  the expert offsets,
-// the per-block start of the token CSR, P, and the capacity flag.
+// Pass 1: per-block (256 consecutive tokens) expert histogram from wave ballots.
 __global__ __launch_bounds__(256) void dispatch_hist_kernel(
-    const uint64_t* __restrict__ mask_bits, int T, int E, int64_t P_cap,
-    int32_t* __restrict__ block_counts,   // [nblk][E] in: counts, out: bases
-    int32_t* __restrict__ tok_base,       // [nblk]
-    int32_t* __restrict__ ticket, int32_t* __restrict__ expert_offsets, int32_t* __restrict__ tok_off,
-    int64_t* __restrict__ num_pairs, int32_t* __restrict__ status)
+    const uint64_t* __restrict__ mask_bits, int T, int E, int32_t* __restrict__ block_counts)
 {
     __shared__ int wc[4][64];
-    __shared__ int is_last;
-    __shared__ int tot[65];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int t = blockIdx.x * kDispatchTokens + tid;
     const uint64_t bits = (t < T) ? mask_bits[t] : 0ull;
@@ -31,18 +23,22 @@ __global__ __launch_bounds__(256) void dispatch_hist_kernel(
     __syncthreads();
     if (tid < E)
         block_counts[(size_t)blockIdx.x * E + tid] = wc[0][tid] + wc[1][tid] + wc[2][tid] + wc[3][tid];
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const int tk = atomicAdd(ticket, 1);
-        __threadfence();
-        is_last = (tk == (int)gridDim.x - 1);
-    }
-    __syncthreads();
-    if (!is_last) return;
+}
 
-    // ---- last block: turn the [nblk][E] histogram table into row bases, in chunks staged through LDS ----
-    const int nblk = gridDim.x;
+// Pass 2 (one block): turns the [nblk][E] histogram table into  base[b][e] = first row of expert e's
+// tokens that live in block b,  the expert offsets, the per-block start of the token CSR, P, and the
+// capacity flag.  (A last-block-done ticket inside pass 1 would serialise one device-scope atomic per
+// block on one address; a separate tiny launch is cheaper.)
+__global__ __launch_bounds__(256) void dispatch_scan_kernel(
+    int nblk, int T, int E, int64_t P_cap,
+    int32_t* __restrict__ block_counts,   // [nblk][E] in: counts, out: bases
+    int32_t* __restrict__ tok_base,       // [nblk]
+    int32_t* __restrict__ expert_offsets, int32_t* __restrict__ tok_off,
+    int64_t* __restrict__ num_pairs, int32_t* __restrict__ status)
+{
+    __shared__ int tot[65];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the table is walked in chunks staged through LDS
     constexpr int kChunkInts = 8192;
     __shared__ int tab[kChunkInts];
     const int rows_per_chunk = min(kChunkInts / E, 256);      // one thread per block row in the scan
@@ -51,7 +47,7 @@ __global__ __launch_bounds__(256) void dispatch_hist_kernel(
     for (int b0 = 0; b0 < nblk; b0 += rows_per_chunk) {
         const int nr = min(rows_per_chunk, nblk - b0);
         for (int i = tid; i < nr * E; i += 256)
-            tab[i] = __hip_atomic_load(&block_counts[(size_t)b0 * E + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            tab[i] = block_counts[(size_t)b0 * E + i];
         __syncthreads();
         if (tid < E)
             for (int r = 0; r < nr; ++r) mysum += tab[r * E + tid];
@@ -66,7 +62,6 @@ __global__ __launch_bounds__(256) void dispatch_hist_kernel(
         *num_pairs = P;
         tok_off[T] = (int32_t)P;
         if (P > P_cap) atomicOr(status, 1);
-        atomicExch(ticket, 0);
     }
     __syncthreads();
     if (tid <= E) expert_offsets[tid] = tot[tid];
@@ -77,7 +72,7 @@ __global__ __launch_bounds__(256) void dispatch_hist_kernel(
     for (int b0 = 0; b0 < nblk; b0 += rows_per_chunk) {
         const int nr = min(rows_per_chunk, nblk - b0);
         for (int i = tid; i < nr * E; i += 256)
-            tab[i] = __hip_atomic_load(&block_counts[(size_t)b0 * E + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            tab[i] = block_counts[(size_t)b0 * E + i];
         __syncthreads();
         // pairs of block b0+tid, then an exclusive scan over the chunk's blocks
         int mine = 0;
@@ -189,9 +184,9 @@ hipError_t launch_dispatch(const Ctx& c, const evomoe_shape& s, const uint64_t* 
     int32_t* tok_base = c.block_counts + (size_t)nblk * s.E;
     {
         ProfScope ps(c, EVOMOE_K_DISPATCH_HIST);
-        hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, s.T, s.E,
-                           s.P_cap, base, tok_base, c.ticket_dev, expert_offsets, tok_off, num_pairs,
-                           c.status_dev);
+        hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, s.T, s.E, base);
+        hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(256), 0, c.stream, nblk, s.T, s.E, s.P_cap, base,
+                           tok_base, expert_offsets, tok_off, num_pairs, c.status_dev);
     }
     {
         ProfScope ps(c, EVOMOE_K_DISPATCH_SCATTER);

@@ -1,9 +1,12 @@
 // DTS gate, forward and backward (EvoMoE Stage 2: Eq. gumbel_softmax, Eq. adaptive_sparsity, Algorithm 2).
 //
-// Forward, one launch: logits on the matrix cores (f32 MFMA, so products and sums keep float32
-// accuracy: a selection decided by g' > c must not move), + bias + Gumbel noise, temperature softmax,
+// Forward: logits on the matrix cores with float32-exact products (f32 MFMA for a float32 layer, three
+// bf16 MFMAs against a hi/mid/lo split of W_g for a bf16 layer: a selection decided by g' > c must not
+// move), + bias + Gumbel noise, temperature softmax,
 // strict threshold with the arg-max fallback, bit mask, per-token k, and the per-expert histogram
 // (per-block partial counts; the last block to finish adds them up in block order).
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace evomoe {
@@ -11,65 +14,29 @@ namespace evomoe {
 // ---------------------------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------------------------
-// Block = 4 waves.  The block owns 16*RT consecutive tokens; each wave takes every 4th K-slab of all
-// of them (v_mfma_f32_16x16x4_f32: A = 16 tokens x 4 k, B = 4 k x 16 experts), the four partial
-// logit tiles are added in wave order through LDS, then 16/RT threads per token do the softmax.
-template <typename TX, int NE, int RT>
-__global__ __launch_bounds__(256) void dts_gate_kernel(
-    const TX* __restrict__ x, const float* __restrict__ Wg, const float* __restrict__ bg,
-    const float* __restrict__ noise, float tau, float c, int T, int d, int E,
-    float* __restrict__ gprime, float* __restrict__ gate_w, uint64_t* __restrict__ mask_bits,
-    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts,
-    int32_t* __restrict__ ticket, int32_t* __restrict__ counts)
+// Common tail of the gate kernels.  In: per-wave partial logit tiles acc[rt][n] (MFMA 16x16 layout:
+// element r of lane (q = lane/16, i16 = lane%16) is token row 4q+r, expert column 16n+i16).
+// Adds the four waves' tiles in wave order (fixed order => reproducible bits), then 16/RT threads per
+// token apply bias, noise, temperature softmax, the strict threshold and the arg-max fallback, write
+// g', weights, mask and k, and build the per-expert histogram (per-block partials, summed by the last
+// block to arrive).
+template <int NE, int RT>
+__device__ __forceinline__ void gate_finish(
+    f32x4 (&acc)[RT][NE], const float* __restrict__ bg, const float* __restrict__ noise, float tau, float c,
+    int T, int E, float* __restrict__ gprime, float* __restrict__ gate_w, uint64_t* __restrict__ mask_bits,
+    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts, int32_t* __restrict__ ticket,
+    int32_t* __restrict__ counts)
 {
-    constexpr int KV = Elem<TX>::kVec;     // k's per 16-byte load
-    constexpr int KB = 4 * KV;             // k's per slab (4 lane groups x KV)
     constexpr int TPB = 16 * RT;           // tokens per block
     constexpr int EP = 16 * NE;            // experts padded to MFMA tiles
     constexpr int LDZ = EP + 4;            // LDS row stride (bank-conflict-free tile writes)
     constexpr int TPT = 256 / TPB;         // threads per token in the softmax phase
     constexpr int EPT = EP / TPT;          // experts per thread there
-
     __shared__ float zsum[TPB * LDZ];
     __shared__ int cnt[64];
-    __shared__ int is_last;
-
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i16 = lane & 15, q = lane >> 4;
     const int t0 = blockIdx.x * TPB;
-
-    f32x4 acc[RT][NE];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-        for (int n = 0; n < NE; ++n) acc[rt][n] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    for (int kb = wave * KB; kb < d; kb += 4 * KB) {
-        const int k0 = kb + q * KV;            // this lane group's first k
-        float a[RT][KV];
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            const int t = t0 + rt * 16 + i16;
-            if (t < T && k0 < d) {
-                Elem<TX>::load_vec(x + (size_t)t * d + k0, a[rt]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < KV; ++j) a[rt][j] = 0.f;
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < KV; ++j) {
-            const int k = k0 + j;
-#pragma unroll
-            for (int n = 0; n < NE; ++n) {
-                const int e = n * 16 + i16;
-                const float b = (k < d && e < E) ? Wg[(size_t)k * E + e] : 0.f;
-#pragma unroll
-                for (int rt = 0; rt < RT; ++rt)
-                    acc[rt][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[rt][j], b, acc[rt][n], 0, 0, 0);
-            }
-        }
-    }
 
     if (tid < 64) cnt[tid] = 0;
     // add the four waves' partial tiles in wave order (fixed order => reproducible bits)
@@ -160,38 +127,166 @@ __global__ __launch_bounds__(256) void dts_gate_kernel(
     }
     __syncthreads();
 
-    // ---- per-expert histogram: per-block partials, summed by the last block to arrive ----
+    // ---- per-expert histogram: per-block partials; gate_counts_kernel adds them up afterwards ----
+    // (a last-block-done ticket would cost one device-scope atomic per block on a single address, which
+    //  at hundreds of blocks takes longer than the whole rest of the kernel)
     if (tid < E) block_counts[(size_t)blockIdx.x * E + tid] = cnt[tid];
-    __threadfence();
+}
+
+// counts[e] = sum over gate blocks of block_counts[b][e]   (one block; integer, order-independent)
+__global__ __launch_bounds__(256) void gate_counts_kernel(const int32_t* __restrict__ block_counts,
+                                                          int nblk, int E, int32_t* __restrict__ counts)
+{
+    __shared__ int cnt[64];
+    const int tid = threadIdx.x;
+    if (tid < 64) cnt[tid] = 0;
     __syncthreads();
-    if (tid == 0) {
-        const int tk = atomicAdd(ticket, 1);
-        __threadfence();
-        is_last = (tk == (int)gridDim.x - 1);
-    }
-    __syncthreads();
-    if (is_last) {
-        // all 256 threads stream the [blocks][E] table (independent, coalesced loads) into LDS counters
-        if (tid < 64) cnt[tid] = 0;
-        __syncthreads();
-        const int total = (int)gridDim.x * E;
-        for (int base = 0; base < total; base += 256 * 8) {
+    // thread -> (column e = tid % EW, row lane tid / EW): private sums first, one LDS atomic per thread
+    const int EW = E <= 16 ? 16 : (E <= 32 ? 32 : 64);
+    const int e = tid % EW, rl = tid / EW, nrl = 256 / EW;
+    int sum = 0;
+    if (e < E)
+        for (int b0 = rl; b0 < nblk; b0 += nrl * 8) {
             int v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int idx = base + u * 256 + tid;
-                v[u] = idx < total ? __hip_atomic_load(&block_counts[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+                const int b = b0 + u * nrl;
+                v[u] = b < nblk ? block_counts[(size_t)b * E + e] : 0;
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = base + u * 256 + tid;
-                if (idx < total && v[u]) atomicAdd(&cnt[idx % E], v[u]);
+            for (int u = 0; u < 8; ++u) sum += v[u];
+        }
+    if (e < E && sum) atomicAdd(&cnt[e], sum);
+    __syncthreads();
+    if (tid < E) counts[tid] = cnt[tid];
+}
+
+// float32 layer: logits with v_mfma_f32_16x16x4_f32 (exact float32 products).  Block = 4 waves; the
+// block owns 16*RT consecutive tokens; each wave takes every 4th K-slab of all of them.
+template <typename TX, int NE, int RT>
+__global__ __launch_bounds__(256) void dts_gate_kernel(
+    const TX* __restrict__ x, const float* __restrict__ Wg, const float* __restrict__ bg,
+    const float* __restrict__ noise, float tau, float c, int T, int d, int E,
+    float* __restrict__ gprime, float* __restrict__ gate_w, uint64_t* __restrict__ mask_bits,
+    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts,
+    int32_t* __restrict__ ticket, int32_t* __restrict__ counts)
+{
+    constexpr int KV = Elem<TX>::kVec;     // k's per 16-byte load
+    constexpr int KB = 4 * KV;             // k's per slab (4 lane groups x KV)
+    constexpr int TPB = 16 * RT;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i16 = lane & 15, q = lane >> 4;
+    const int t0 = blockIdx.x * TPB;
+
+    f32x4 acc[RT][NE];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int n = 0; n < NE; ++n) acc[rt][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int kb = wave * KB; kb < d; kb += 4 * KB) {
+        const int k0 = kb + q * KV;            // this lane group's first k
+        float a[RT][KV];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const int t = t0 + rt * 16 + i16;
+            if (t < T && k0 < d) {
+                Elem<TX>::load_vec(x + (size_t)t * d + k0, a[rt]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < KV; ++j) a[rt][j] = 0.f;
             }
         }
-        __syncthreads();
-        if (tid < E) counts[tid] = cnt[tid];
-        if (tid == 0) atomicExch(ticket, 0);     // ready for the next launch on this stream
+#pragma unroll
+        for (int j = 0; j < KV; ++j) {
+            const int k = k0 + j;
+#pragma unroll
+            for (int n = 0; n < NE; ++n) {
+                const int e = n * 16 + i16;
+                const float b = (k < d && e < E) ? Wg[(size_t)k * E + e] : 0.f;
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                    acc[rt][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[rt][j], b, acc[rt][n], 0, 0, 0);
+            }
+        }
     }
+    gate_finish<NE, RT>(acc, bg, noise, tau, c, T, E, gprime, gate_w, mask_bits, k_per_token, block_counts,
+                        ticket, counts);
+}
+
+// bf16 layer.  x is exact in bf16, so W_g is split into three bf16 terms (hi + mid + lo carry all 24
+// mantissa bits of the float32 weight) and the logits come from three v_mfma_f32_16x16x32_bf16 per 32 k's:
+// every product is exact in float32 and the sum is accumulated in float32 -- the same accuracy as float32
+// FMAs, at matrix-core rate, which keeps the kernel HBM-bound up to E = 64.  The split, transposed copy of
+// W_g ([3][16*NE][d] bf16, zero rows beyond E) is made by split_wg_kernel right before.
+__global__ __launch_bounds__(256) void split_wg_kernel(const float* __restrict__ Wg, int d, int E, int EP,
+                                                       uint16_t* __restrict__ planes)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;          // over EP * d, k fastest
+    if (i >= EP * d) return;
+    const int e = i / d, k = i % d;
+    const float w = e < E ? Wg[(size_t)k * E + e] : 0.f;
+    const uint32_t hi = f32_to_bf16_bits(w);
+    const float r1 = w - bf16_bits_to_f32(hi);
+    const uint32_t mid = f32_to_bf16_bits(r1);
+    const float r2 = r1 - bf16_bits_to_f32(mid);
+    const uint32_t lo = f32_to_bf16_bits(r2);
+    const size_t plane = (size_t)EP * d;
+    planes[i] = (uint16_t)hi;
+    planes[plane + i] = (uint16_t)mid;
+    planes[2 * plane + i] = (uint16_t)lo;
+}
+
+template <int NE, int RT>
+__global__ __launch_bounds__(256) void dts_gate_bf16_kernel(
+    const bf16_t* __restrict__ x, const bf16_t* __restrict__ planes, const float* __restrict__ bg,
+    const float* __restrict__ noise, float tau, float c, int T, int d, int E,
+    float* __restrict__ gprime, float* __restrict__ gate_w, uint64_t* __restrict__ mask_bits,
+    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts,
+    int32_t* __restrict__ ticket, int32_t* __restrict__ counts)
+{
+    constexpr int TPB = 16 * RT, EP = 16 * NE;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i16 = lane & 15, q = lane >> 4;
+    const int t0 = blockIdx.x * TPB;
+    const size_t plane = (size_t)EP * d;
+
+    f32x4 acc[RT][NE];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int n = 0; n < NE; ++n) acc[rt][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const bf16x8 zero8 = {};
+    // k-blocks of 32, dealt round-robin to the four waves; lane group q holds k = 32*kb + 8q .. +7
+    for (int kb = wave; kb * 32 < d; kb += 4) {
+        const int k0 = kb * 32 + q * 8;
+        const bool kok = k0 < d;
+        bf16x8 a[RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const int t = t0 + rt * 16 + i16;
+            a[rt] = (kok && t < T) ? *reinterpret_cast<const bf16x8*>(x + (size_t)t * d + k0) : zero8;
+        }
+#pragma unroll
+        for (int n = 0; n < NE; ++n) {
+            const bf16_t* wp = planes + (size_t)(n * 16 + i16) * d + k0;
+            bf16x8 b0 = zero8, b1 = zero8, b2 = zero8;
+            if (kok) {
+                b0 = *reinterpret_cast<const bf16x8*>(wp);
+                b1 = *reinterpret_cast<const bf16x8*>(wp + plane);
+                b2 = *reinterpret_cast<const bf16x8*>(wp + 2 * plane);
+            }
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                acc[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b2, acc[rt][n], 0, 0, 0);
+                acc[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b1, acc[rt][n], 0, 0, 0);
+                acc[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b0, acc[rt][n], 0, 0, 0);
+            }
+        }
+    }
+    gate_finish<NE, RT>(acc, bg, noise, tau, c, T, E, gprime, gate_w, mask_bits, k_per_token, block_counts,
+                        ticket, counts);
 }
 
 static int pick_rt(const Ctx& c, int T) {
@@ -213,9 +308,19 @@ static hipError_t gate_launch_t(const Ctx& c, const evomoe_shape& s, const void*
                                 int32_t* k_per_token) {
     const int blocks = (s.T + 16 * RT - 1) / (16 * RT);
     ProfScope ps(c, EVOMOE_K_GATE);
-    hipLaunchKernelGGL((dts_gate_kernel<TX, NE, RT>), dim3(blocks), dim3(256), 0, c.stream,
-                       (const TX*)x, Wg, bg, noise, tau, thr, s.T, s.d, s.E, gprime, gate_w,
-                       mask_bits, k_per_token, c.block_counts, c.ticket_dev, counts);
+    if constexpr (std::is_same<TX, bf16_t>::value) {
+        const int ep = 16 * NE;
+        hipLaunchKernelGGL(split_wg_kernel, dim3((ep * s.d + 255) / 256), dim3(256), 0, c.stream, Wg, s.d,
+                           s.E, ep, c.wg_planes);
+        hipLaunchKernelGGL((dts_gate_bf16_kernel<NE, RT>), dim3(blocks), dim3(256), 0, c.stream,
+                           (const bf16_t*)x, (const bf16_t*)c.wg_planes, bg, noise, tau, thr, s.T, s.d, s.E,
+                           gprime, gate_w, mask_bits, k_per_token, c.block_counts, c.ticket_dev, counts);
+    } else {
+        hipLaunchKernelGGL((dts_gate_kernel<TX, NE, RT>), dim3(blocks), dim3(256), 0, c.stream,
+                           (const TX*)x, Wg, bg, noise, tau, thr, s.T, s.d, s.E, gprime, gate_w,
+                           mask_bits, k_per_token, c.block_counts, c.ticket_dev, counts);
+    }
+    hipLaunchKernelGGL(gate_counts_kernel, dim3(1), dim3(256), 0, c.stream, c.block_counts, blocks, s.E, counts);
     return hipGetLastError();
 }
 
