@@ -142,6 +142,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
     constexpr bool PF = (WPE == 1 && BK == 64 && BM == 256);
     constexpr int PFD = 2;
     constexpr int NPF = !PF ? 0 : (LAYOUT == L_TN ? 2 : 1);
+    constexpr bool SPLIT_LD = NSTAGE >= 3 && !PF;   // half of a slab's loads before the barrier, half after
     static_assert(BK == 32 || BK == 64, "slab");
     static_assert(WM % 32 == 0 && WN % 32 == 0 && A_LD >= 1 && B_LD >= 1 && NSTAGE >= 2 && KS % 2 == 0, "tile");
     static_assert((NSTAGE - 2) * NLD + (NSTAGE - 1) * 2 <= 63, "vmcnt range");
@@ -382,7 +383,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
         // share of the next k-step's fragment reads (into NA, NB; slab nslb, k-step nks) is issued, and
         // after every group, optionally, a share of a later slab's global->LDS loads.  The scheduling
         // fences pin this order.
-#define KSTEP(FA, FB, READ_NEXT, NA, NB, nslb, nks, LOADS, lslab)                                 \
+#define KSTEP(FA, FB, READ_NEXT, NA, NB, nslb, nks, LD_LO, LD_HI, lslab)                          \
     _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                              \
         _Pragma("unroll") for (int x = NMF * q / 8; x < NMF * (q + 1) / 8; ++x)                  \
             acc[x / TN_][x % TN_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                     \
@@ -391,10 +392,9 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             _Pragma("unroll") for (int f = NFR * q / 4; f < NFR * (q + 1) / 4; ++f)              \
                 read_frag(f, nslb, nks, NA, NB);                                                 \
         }                                                                                        \
-        if (LOADS) {                                                                             \
-            _Pragma("unroll") for (int x = NLD * q / 8; x < NLD * (q + 1) / 8; ++x)              \
-                issue_one(x, lslab);                                                             \
-        }                                                                                        \
+        _Pragma("unroll") for (int x = (LD_LO) + ((LD_HI) - (LD_LO)) * q / 8;                    \
+                               x < (LD_LO) + ((LD_HI) - (LD_LO)) * (q + 1) / 8; ++x)             \
+            issue_one(x, lslab);                                                                 \
         __builtin_amdgcn_sched_barrier(0);                                                       \
     }
 
@@ -423,31 +423,34 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
         // s-1 has finished with; before the last k-step the block makes sure slab s+1 has landed.
         auto slab_body = [&](int slab, auto loads_c) {
             constexpr bool LOADS = decltype(loads_c)::value;
-            KSTEP(fa0, fb0, true, fa1, fb1, slab, 1, LOADS, slab + NSTAGE - 1);
+            // with three or more stages the second half of a slab's loads goes out after the barrier
+            // (its stage was released one slab earlier), which keeps the load unit evenly busy
+            constexpr int L0 = !LOADS ? 0 : (SPLIT_LD ? NLD / 2 : NLD), L1 = LOADS ? NLD : 0;
+            KSTEP(fa0, fb0, true, fa1, fb1, slab, 1, 0, L0, slab + NSTAGE - 1);
             if (LOADS) prefetch(slab + NSTAGE - 1 + PFD);
             if (KS == 4) {
-                KSTEP(fa1, fb1, true, fa0, fb0, slab, 2, false, 0);
-                KSTEP(fa0, fb0, true, fa1, fb1, slab, 3, false, 0);
+                KSTEP(fa1, fb1, true, fa0, fb0, slab, 2, 0, 0, 0);
+                KSTEP(fa0, fb0, true, fa1, fb1, slab, 3, 0, 0, 0);
             }
             // everything issued after slab+1's loads may still be in flight
-            if (LOADS) wait_vmcnt<(NSTAGE - 2) * NLD + (NSTAGE - 1) * NPF>(); else wait_vmcnt<0>();
+            if (LOADS) wait_vmcnt<(NSTAGE - 2) * NLD - (NLD - L0) + (NSTAGE - 1) * NPF>(); else wait_vmcnt<0>();
             block_sync_lds();
             if (slab + 2 == nslab && ragged) {
                 zero_tail(slab + 1);
                 block_sync_lds();
             }
-            KSTEP(fa1, fb1, true, fa0, fb0, slab + 1, 0, false, 0);
+            KSTEP(fa1, fb1, true, fa0, fb0, slab + 1, 0, L0, L1, slab + NSTAGE - 1);
         };
         int slab = 0;
         for (; slab + NSTAGE - 1 < nslab; ++slab) slab_body(slab, std::true_type{});
         for (; slab + 1 < nslab; ++slab) slab_body(slab, std::false_type{});
         if (nslab > 0) {           // last slab: nothing left to fetch or to read ahead
-            KSTEP(fa0, fb0, true, fa1, fb1, slab, 1, false, 0);
+            KSTEP(fa0, fb0, true, fa1, fb1, slab, 1, 0, 0, 0);
             if (KS == 4) {
-                KSTEP(fa1, fb1, true, fa0, fb0, slab, 2, false, 0);
-                KSTEP(fa0, fb0, true, fa1, fb1, slab, 3, false, 0);
+                KSTEP(fa1, fb1, true, fa0, fb0, slab, 2, 0, 0, 0);
+                KSTEP(fa0, fb0, true, fa1, fb1, slab, 3, 0, 0, 0);
             }
-            KSTEP(fa1, fb1, false, fa0, fb0, 0, 0, false, 0);
+            KSTEP(fa1, fb1, false, fa0, fb0, 0, 0, 0, 0, 0);
         }
 #undef KSTEP
         __syncthreads();          // every wave is done reading operands: LDS becomes the epilogue's staging area
@@ -458,8 +461,32 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
         float* stg = reinterpret_cast<float*>(smem) + wave * (ER * G::EPI_LD);
         constexpr int CPW = WN / 8;                 // 8-column chunks per wave-tile row
         constexpr int RPI = 64 / CPW;               // rows finished per instruction
+        constexpr int NIT = ER / RPI;               // store instructions per pass
+        constexpr int EPI_UNROLL = NIT <= 8 ? NIT : 4;
+        // this lane's 8 columns are the same in every pass and iteration; loads that feed the epilogue are
+        // issued ahead of the loop that stores (a load after a store of unknown aliasing is not hoisted)
+        const int lc = (lane % CPW) * 8;
+        const int col = n0 + wn * WN + lc;
+        const int col_c = min(col, p.N - 8);
+        float bias8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if ((EPI == E_HA || EPI == E_BIAS) && LAYOUT != L_TN) {
+            if (p.bias) {
+                const f32x4 b0 = *reinterpret_cast<const f32x4*>(p.bias + (int64_t)g * p.N + col_c);
+                const f32x4 b1 = *reinterpret_cast<const f32x4*>(p.bias + (int64_t)g * p.N + col_c + 4);
+                bias8[0] = b0.x; bias8[1] = b0.y; bias8[2] = b0.z; bias8[3] = b0.w;
+                bias8[4] = b1.x; bias8[5] = b1.y; bias8[6] = b1.z; bias8[7] = b1.w;
+            }
+        }
 #pragma unroll
         for (int pass = 0; pass < WM / ER; ++pass) {
+            u32x4 hraw[EPI == E_ACTGRAD ? NIT : 1];
+            if (EPI == E_ACTGRAD) {
+#pragma unroll
+                for (int it = 0; it < NIT; ++it) {
+                    const int trow = min(wm * WM + pass * ER + it * RPI + lane / CPW, rows - 1);
+                    hraw[it] = *reinterpret_cast<const u32x4*>(p.Hin + (int64_t)(row0 + trow) * p.N + col_c);
+                }
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -472,12 +499,10 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
                 }
             __builtin_amdgcn_s_waitcnt(0xc07f);     // this wave's LDS writes are done (lgkmcnt(0))
             __builtin_amdgcn_wave_barrier();
-#pragma unroll 4
-            for (int it = 0; it < ER / RPI; ++it) {
+#pragma unroll EPI_UNROLL
+            for (int it = 0; it < NIT; ++it) {
                 const int lr = it * RPI + lane / CPW;            // row inside the pass
-                const int lc = (lane % CPW) * 8;                 // first of 8 columns
                 const int trow = wm * WM + pass * ER + lr;       // row inside the block tile
-                const int col = n0 + wn * WN + lc;
                 const f32x4 v0 = *reinterpret_cast<const f32x4*>(stg + lr * G::EPI_LD + lc);
                 const f32x4 v1 = *reinterpret_cast<const f32x4*>(stg + lr * G::EPI_LD + lc + 4);
                 float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
@@ -497,24 +522,32 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
                     if (trow >= rows) continue;
                     const int64_t grow = (int64_t)(row0 + trow);
                     if (EPI == E_HA || EPI == E_BIAS) {
-                        if (p.bias) {
-                            const f32x4 b0 = *reinterpret_cast<const f32x4*>(p.bias + (int64_t)g * p.N + col);
-                            const f32x4 b1 = *reinterpret_cast<const f32x4*>(p.bias + (int64_t)g * p.N + col + 4);
-                            v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
-                            v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
-                        }
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) v[q] += bias8[q];
                     }
                     if (EPI == E_ACTGRAD) {
-                        float h[8];
-                        Elem<bf16_t>::load_vec(p.Hin + grow * p.N + col, h);
+                        const u32x4 hw = hraw[it];
+                        const float h[8] = {lo_bf16(hw.x), hi_bf16(hw.x), lo_bf16(hw.y), hi_bf16(hw.y),
+                                            lo_bf16(hw.z), hi_bf16(hw.z), lo_bf16(hw.w), hi_bf16(hw.w)};
+                        // one branch per eight values (not per value): the eight polynomial chains interleave
+                        if (p.act == EVOMOE_RELU) {
 #pragma unroll
-                        for (int q = 0; q < 8; ++q) v[q] *= act_grad_fast(h[q], p.act);
+                            for (int q = 0; q < 8; ++q) v[q] *= act_grad_fast(h[q], EVOMOE_RELU);
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < 8; ++q) v[q] *= act_grad_fast(h[q], EVOMOE_GELU_ERF);
+                        }
                     }
                     Elem<bf16_t>::store_vec(p.out1 + grow * p.N + col, v);
                     if (EPI == E_HA) {
                         float a[8];
+                        if (p.act == EVOMOE_RELU) {
 #pragma unroll
-                        for (int q = 0; q < 8; ++q) a[q] = act_fwd_fast(v[q], p.act);
+                            for (int q = 0; q < 8; ++q) a[q] = act_fwd_fast(v[q], EVOMOE_RELU);
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < 8; ++q) a[q] = act_fwd_fast(v[q], EVOMOE_GELU_ERF);
+                        }
                         Elem<bf16_t>::store_vec(p.out2 + grow * p.N + col, a);
                     }
                 }
