@@ -22,6 +22,13 @@ evomoe_status check_shape(const evomoe_shape* s) {
     const int vec = s->dtype == EVOMOE_BF16 ? 8 : 4;
     if (s->d % vec || s->F % vec) return EVOMOE_EUNSUPPORTED;
     if ((int64_t)s->T * s->E > INT32_MAX || s->P_cap > INT32_MAX) return EVOMOE_EUNSUPPORTED;
+    if (s->dtype == EVOMOE_BF16) {
+        // the MFMA kernels address operands as a 64-bit tile base plus 32-bit byte offsets per lane, and
+        // their k-contiguous tiles need at least one full 64-wide slab
+        const int64_t lim = (int64_t)1 << 32, wide = s->d > s->F ? s->d : s->F;
+        if (s->d < 64 || s->F < 64) return EVOMOE_EUNSUPPORTED;
+        if ((int64_t)s->T * wide * 2 >= lim || (int64_t)s->d * s->F * 2 >= lim) return EVOMOE_EUNSUPPORTED;
+    }
     return EVOMOE_OK;
 }
 

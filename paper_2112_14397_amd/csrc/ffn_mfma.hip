@@ -105,9 +105,10 @@ __device__ __forceinline__ float act_grad_fast(float h, int act) {
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
-__device__ __forceinline__ void load_to_lds(const bf16_t* gptr, const unsigned char* lds_wave_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(gptr), "s"(lds_addr(lds_wave_base)) : "m0", "memory");
+// The global address is a wave-uniform base (an SGPR pair) plus a 32-bit unsigned byte offset per lane.
+__device__ __forceinline__ void load_to_lds(const unsigned char* base, uint32_t voff, const unsigned char* lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(base), "s"(lds_addr(lds_wave_base)) : "m0", "memory");
 }
 __device__ __forceinline__ void touch_to_lds(const bf16_t* gptr, const unsigned char* lds_wave_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
@@ -234,44 +235,52 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             kbeg = 0;
             kend = p.K;
         }
+        // the tile's coordinates came through LDS: tell the compiler they are wave-uniform (SGPRs)
+        g = __builtin_amdgcn_readfirstlane(g);
+        row0 = __builtin_amdgcn_readfirstlane(row0);
+        rows = __builtin_amdgcn_readfirstlane(rows);
+        kbeg = __builtin_amdgcn_readfirstlane(kbeg);
+        kend = __builtin_amdgcn_readfirstlane(kend);
         const int nslab = (kend - kbeg + BK - 1) / BK;
         const bool ragged = (kend - kbeg) % BK != 0;     // block-uniform: the last slab is partial
         const bf16_t* Bg = (LAYOUT == L_TN) ? p.B : p.B + (int64_t)g * p.b_group_stride;
 
-        // ---------------- per-lane global addresses of slab 0 ----------------
+        // ---------------- global addresses: one scalar base per operand + 32-bit per-lane byte offsets ----
         // Rows / columns outside the tile are clamped onto valid ones (their products are never stored);
         // the tail of the contraction range is clamped too and then zeroed in LDS (A operand only).
-        const bf16_t* a_ptr[A_LD];
-        const bf16_t* b_ptr[B_LD];
+        // k-contiguous operand: offset of (row, chunk) at k = 0, one register per load instruction.
+        // k-strided operand   : offset = k-row * row bytes + column bytes; every load instruction of a lane
+        //                       has the same column, its k-row is kr0 + a constant.
+        const unsigned char* a_base;
+        const unsigned char* b_base;
+        uint32_t a_off[G::A_KC ? A_LD : 1], b_off[G::B_KC ? B_LD : 1];
+        uint32_t a_col = 0, b_col = 0;                    // k-strided: column byte offset
         if (G::A_KC) {
+            a_base = reinterpret_cast<const unsigned char*>(p.A) + (p.a_rows ? (int64_t)0 : (int64_t)row0 * p.lda * 2);
 #pragma unroll
             for (int i = 0; i < A_LD; ++i) {
                 const int r = min((wave + 4 * i) * KC_RPI + kc_row, rows - 1);
-                const int64_t ar = p.a_rows ? (int64_t)p.a_rows[row0 + r] : (int64_t)(row0 + r);
-                a_ptr[i] = p.A + ar * p.lda + kc_chunk * 8;
+                const uint32_t ar = p.a_rows ? (uint32_t)p.a_rows[row0 + r] : (uint32_t)r;
+                a_off[i] = (ar * (uint32_t)p.lda + kc_chunk * 8) * 2;
             }
         } else {
-#pragma unroll
-            for (int i = 0; i < A_LD; ++i) {
-                const int kr = (wave + 4 * i) * A_RPI + ksA_row;
-                const int m = min(m0 + ks_col(lane % A_CPR, kr), p.M - 8);
-                a_ptr[i] = p.A + (int64_t)(kbeg + kr) * p.lda + m;
-            }
+            a_base = reinterpret_cast<const unsigned char*>(p.A) + (int64_t)kbeg * p.lda * 2;
+            a_col = 2 * min(m0 + ks_col(lane % A_CPR, wave * A_RPI + ksA_row), p.M - 8);
         }
         if (G::B_KC) {
+            b_base = reinterpret_cast<const unsigned char*>(Bg);
 #pragma unroll
             for (int i = 0; i < B_LD; ++i) {
                 const int n = min(n0 + (wave + 4 * i) * KC_RPI + kc_row, p.N - 1);
-                b_ptr[i] = Bg + (int64_t)n * p.ldb + kc_chunk * 8;
+                b_off[i] = ((uint32_t)n * (uint32_t)p.ldb + kc_chunk * 8) * 2;
             }
         } else {
-#pragma unroll
-            for (int i = 0; i < B_LD; ++i) {
-                const int kr = (wave + 4 * i) * B_RPI + ksB_row;
-                const int n = min(n0 + ks_col(lane % B_CPR, kr), p.N - 8);
-                b_ptr[i] = Bg + n + (int64_t)(kbeg + kr) * p.ldb;
-            }
+            b_base = reinterpret_cast<const unsigned char*>(Bg) + (int64_t)kbeg * p.ldb * 2;
+            b_col = 2 * min(n0 + ks_col(lane % B_CPR, wave * B_RPI + ksB_row), p.N - 8);
         }
+        const int klen = kend - kbeg;
+        const int kc_lim = 2 * (kend - 8 - kc_chunk * 8);        // k-contiguous: last in-range chunk start (bytes)
+        const uint32_t lda2 = (uint32_t)p.lda * 2, ldb2 = (uint32_t)p.ldb * 2;
         // prefetch addresses: k-contiguous A: thread = tile row (one 128 B line per row and slab);
         // k-strided (TN): thread = (k-row tid/4, 128 B segment tid%4) of the 64 x 512 B slab
         const bf16_t* pf_a = p.A;
@@ -302,22 +311,21 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
         auto issue_one = [&](int idx, int slab) {
             unsigned char* sa = smem + (slab % NSTAGE) * G::STAGE + wave * 1024;
             unsigned char* sb = sa + G::A_BYTES;
-            const int k0 = kbeg + slab * BK;            // absolute first k (row) of the slab
             if (idx < A_LD) {
                 const int i = idx;
                 if (G::A_KC) {
-                    load_to_lds(a_ptr[i] + min(slab * BK, kend - 8 - kc_chunk * 8), sa + i * 4096);
+                    load_to_lds(a_base, a_off[i] + (uint32_t)min(slab * (BK * 2), kc_lim), sa + i * 4096);
                 } else {
-                    const int kr = (wave + 4 * i) * A_RPI + ksA_row;
-                    load_to_lds(a_ptr[i] + (int64_t)(min(k0 + kr, kend - 1) - (kbeg + kr)) * p.lda, sa + i * 4096);
+                    const int kr = min(slab * BK + (wave + 4 * i) * A_RPI + ksA_row, klen - 1);
+                    load_to_lds(a_base, __umul24((uint32_t)kr, lda2) + a_col, sa + i * 4096);
                 }
             } else {
                 const int i = idx - A_LD;
                 if (G::B_KC) {
-                    load_to_lds(b_ptr[i] + min(slab * BK, kend - 8 - kc_chunk * 8), sb + i * 4096);
+                    load_to_lds(b_base, b_off[i] + (uint32_t)min(slab * (BK * 2), kc_lim), sb + i * 4096);
                 } else {
-                    const int kr = (wave + 4 * i) * B_RPI + ksB_row;
-                    load_to_lds(b_ptr[i] + (int64_t)(min(k0 + kr, kend - 1) - (kbeg + kr)) * p.ldb, sb + i * 4096);
+                    const int kr = min(slab * BK + (wave + 4 * i) * B_RPI + ksB_row, klen - 1);
+                    load_to_lds(b_base, __umul24((uint32_t)kr, ldb2) + b_col, sb + i * 4096);
                 }
             }
         };
@@ -398,7 +406,9 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
         __builtin_amdgcn_sched_barrier(0);                                                       \
     }
 
-        __syncthreads();          // previous tile's epilogue has left the LDS (and its stores are on their way)
+        // previous tile's epilogue has left the LDS; its global stores stay in flight under this tile's
+        // first loads (a full barrier would drain them first)
+        block_sync_lds();
         bf16x8 fa0[TM], fb0[TN_], fa1[TM], fb1[TN_];
         if (nslab > 0) {
             // prologue: put NSTAGE-1 slabs in flight, wait for the first
@@ -453,7 +463,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             KSTEP(fa1, fb1, false, fa0, fb0, 0, 0, 0, 0, 0);
         }
 #undef KSTEP
-        __syncthreads();          // every wave is done reading operands: LDS becomes the epilogue's staging area
+        block_sync_lds();         // every wave is done reading operands: LDS becomes the epilogue's staging area
 
         // ---------------- epilogue: stage f32 rows through LDS, finish row-major ----------------
         // acc[i][j][r] is C(row = i*32 + 8*(r/4) + 4*kg + r%4, col = j*32 + l32) of the wave tile.
@@ -506,21 +516,22 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
                 const f32x4 v0 = *reinterpret_cast<const f32x4*>(stg + lr * G::EPI_LD + lc);
                 const f32x4 v1 = *reinterpret_cast<const f32x4*>(stg + lr * G::EPI_LD + lc + 4);
                 float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-                if (col >= p.N) continue;
+                // the arithmetic runs for every lane (out-of-tile lanes on clamped addresses); only the
+                // stores are predicated, so no wait for a load ends up inside divergent control flow
                 if (LAYOUT == L_TN) {
                     const int m = m0 + trow;
-                    if (m >= p.M) continue;
-                    bf16_t* dst = p.out1 + ((int64_t)g * p.M + m) * p.N + col;
+                    const bool ok = col < p.N && m < p.M;
+                    bf16_t* dst = p.out1 + ((int64_t)g * p.M + min(m, p.M - 1)) * p.N + col_c;
                     if (p.accumulate) {
                         float old[8];
                         Elem<bf16_t>::load_vec(dst, old);
 #pragma unroll
                         for (int q = 0; q < 8; ++q) v[q] += old[q];
                     }
-                    Elem<bf16_t>::store_vec(dst, v);
+                    if (ok) Elem<bf16_t>::store_vec(dst, v);
                 } else {
-                    if (trow >= rows) continue;
-                    const int64_t grow = (int64_t)(row0 + trow);
+                    const bool ok = col < p.N && trow < rows;
+                    const int64_t grow = (int64_t)(row0 + min(trow, rows - 1));
                     if (EPI == E_HA || EPI == E_BIAS) {
 #pragma unroll
                         for (int q = 0; q < 8; ++q) v[q] += bias8[q];
@@ -538,7 +549,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
                             for (int q = 0; q < 8; ++q) v[q] *= act_grad_fast(h[q], EVOMOE_GELU_ERF);
                         }
                     }
-                    Elem<bf16_t>::store_vec(p.out1 + grow * p.N + col, v);
+                    if (ok) Elem<bf16_t>::store_vec(p.out1 + grow * p.N + col_c, v);
                     if (EPI == E_HA) {
                         float a[8];
                         if (p.act == EVOMOE_RELU) {
@@ -548,7 +559,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
 #pragma unroll
                             for (int q = 0; q < 8; ++q) a[q] = act_fwd_fast(v[q], EVOMOE_GELU_ERF);
                         }
-                        Elem<bf16_t>::store_vec(p.out2 + grow * p.N + col, a);
+                        if (ok) Elem<bf16_t>::store_vec(p.out2 + grow * p.N + col_c, a);
                     }
                 }
             }
