@@ -334,7 +334,10 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             for (int idx = 0; idx < NLD; ++idx) issue_one(idx, slab);
         };
         // zero the A operand beyond the end of the contraction range (last slab only)
-        auto zero_tail = [&](int slab) {
+        // (always the tile's last slab: its position comes from the tile, not from the loop counter, so that
+        // no per-lane induction variable is carried through the main loop for this rare path)
+        auto zero_tail = [&]() {
+            const int slab = nslab - 1;
             unsigned char* sa = smem + (slab % NSTAGE) * G::STAGE + wave * 1024;
             const int k0 = kbeg + slab * BK;
             const u32x4 z = {0u, 0u, 0u, 0u};
@@ -409,6 +412,10 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
         // previous tile's epilogue has left the LDS; its global stores stay in flight under this tile's
         // first loads (a full barrier would drain them first)
         block_sync_lds();
+        // Every load the compiler itself issued during the tile set-up (row indices, spill reloads) has to be
+        // complete, and known to it as complete, before the pipeline starts: a wait that it places inside
+        // the main loop for one of its own loads would also wait for the tile loads issued there.
+        __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0)
         bf16x8 fa0[TM], fb0[TN_], fa1[TM], fb1[TN_];
         if (nslab > 0) {
             // prologue: put NSTAGE-1 slabs in flight, wait for the first
@@ -421,7 +428,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             if (nslab >= NSTAGE - 1 && NPF == 0) wait_vmcnt<(NSTAGE - 2) * NLD>(); else wait_vmcnt<0>();
             block_sync_lds();
             if (nslab == 1 && ragged) {
-                zero_tail(0);
+                zero_tail();
                 block_sync_lds();
             }
 #pragma unroll
@@ -446,7 +453,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             if (LOADS) wait_vmcnt<(NSTAGE - 2) * NLD - (NLD - L0) + (NSTAGE - 1) * NPF>(); else wait_vmcnt<0>();
             block_sync_lds();
             if (slab + 2 == nslab && ragged) {
-                zero_tail(slab + 1);
+                zero_tail();
                 block_sync_lds();
             }
             KSTEP(fa1, fb1, true, fa0, fb0, slab + 1, 0, L0, L1, slab + NSTAGE - 1);
@@ -507,7 +514,9 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
                     for (int j = 0; j < TN_; ++j)
                         stg[(wrow % ER + 4 * kg + (r & 3)) * G::EPI_LD + j * 32 + l32] = acc[i][j][r];
                 }
-            __builtin_amdgcn_s_waitcnt(0xc07f);     // this wave's LDS writes are done (lgkmcnt(0))
+            // this wave's LDS writes are done -- and so are the loads issued above: waiting for them one by
+            // one between the stores below would also wait for those stores (one counter covers both)
+            __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0) lgkmcnt(0)
             __builtin_amdgcn_wave_barrier();
 #pragma unroll EPI_UNROLL
             for (int it = 0; it < NIT; ++it) {
@@ -601,10 +610,10 @@ template <class Cfg> int64_t mtiles(int m) { return (m + Cfg::BM - 1) / Cfg::BM;
 
 #ifndef EVOMOE_CFG_GEMM1
 #define EVOMOE_CFG_GEMM1 CfgDuo
-#define EVOMOE_CFG_GEMM2 CfgBig
+#define EVOMOE_CFG_GEMM2 CfgBig4
 #define EVOMOE_CFG_DH CfgDuo
-#define EVOMOE_CFG_DX CfgBig
-#define EVOMOE_CFG_DW CfgBig
+#define EVOMOE_CFG_DX CfgBig4
+#define EVOMOE_CFG_DW CfgBig4
 #endif
 
 }  // namespace
