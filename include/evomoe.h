@@ -35,8 +35,10 @@
  *    EVOMOE_ECAPACITY.
  *  - Identical inputs give bit-identical outputs (no floating-point atomics).
  *  - Limits: 1 <= E <= 64; d and F multiples of 8 (bf16) or 4 (f32);
- *    T*E and P_cap*max(d,F) below 2^31 rows*cols is NOT required (64-bit
- *    indexing), but T and P_cap must be below 2^31.
+ *    T*E and P_cap below 2^31 (P_cap*max(d,F) may exceed 2^31: row bases are
+ *    64-bit).  The bf16 expert FFN (forward and backward) additionally needs
+ *    d >= 64, F >= 64, and T*max(d,F)*2 and d*F*2 below 2^32 bytes (inside a
+ *    tile its kernels add 32-bit byte offsets to a 64-bit base).
  */
 #ifndef EVOMOE_H
 #define EVOMOE_H

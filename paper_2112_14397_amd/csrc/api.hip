@@ -22,13 +22,16 @@ evomoe_status check_shape(const evomoe_shape* s) {
     const int vec = s->dtype == EVOMOE_BF16 ? 8 : 4;
     if (s->d % vec || s->F % vec) return EVOMOE_EUNSUPPORTED;
     if ((int64_t)s->T * s->E > INT32_MAX || s->P_cap > INT32_MAX) return EVOMOE_EUNSUPPORTED;
-    if (s->dtype == EVOMOE_BF16) {
-        // the MFMA kernels address operands as a 64-bit tile base plus 32-bit byte offsets per lane, and
-        // their k-contiguous tiles need at least one full 64-wide slab
-        const int64_t lim = (int64_t)1 << 32, wide = s->d > s->F ? s->d : s->F;
-        if (s->d < 64 || s->F < 64) return EVOMOE_EUNSUPPORTED;
-        if ((int64_t)s->T * wide * 2 >= lim || (int64_t)s->d * s->F * 2 >= lim) return EVOMOE_EUNSUPPORTED;
-    }
+    return EVOMOE_OK;
+}
+
+// Extra limits of the bf16 expert FFN: its MFMA kernels address operands as a 64-bit tile base plus 32-bit
+// byte offsets per lane, and their k-contiguous tiles need at least one full 64-wide slab.
+evomoe_status check_ffn_shape(const evomoe_shape* s) {
+    if (s->dtype != EVOMOE_BF16) return EVOMOE_OK;
+    const int64_t lim = (int64_t)1 << 32, wide = s->d > s->F ? s->d : s->F;
+    if (s->d < 64 || s->F < 64) return EVOMOE_EUNSUPPORTED;
+    if ((int64_t)s->T * wide * 2 >= lim || (int64_t)s->d * s->F * 2 >= lim) return EVOMOE_EUNSUPPORTED;
     return EVOMOE_OK;
 }
 
@@ -188,6 +191,7 @@ evomoe_status evomoe_expert_ffn(evomoe_ctx* ctx, const evomoe_shape* shape, cons
                                 const void* W1, const float* b1, const void* W2, const float* b2,
                                 void* H, void* A, void* O) {
     CHECK_CTX_SHAPE();
+    if (evomoe_status fs = check_ffn_shape(shape); fs != EVOMOE_OK) return fs;
     REQUIRE_PTR(x); REQUIRE_PTR(expert_offsets); REQUIRE_PTR(W1); REQUIRE_PTR(W2);
     REQUIRE_PTR(H); REQUIRE_PTR(A); REQUIRE_PTR(O);
     OPTIONAL_PTR(pair_token); OPTIONAL_PTR(b1); OPTIONAL_PTR(b2);
@@ -218,6 +222,7 @@ evomoe_status evomoe_expert_ffn_bwd(evomoe_ctx* ctx, const evomoe_shape* shape, 
                                     float* db2, void* dXp, int accumulate, void* workspace,
                                     size_t workspace_bytes) {
     CHECK_CTX_SHAPE();
+    if (evomoe_status fs = check_ffn_shape(shape); fs != EVOMOE_OK) return fs;
     REQUIRE_PTR(dO); REQUIRE_PTR(H); REQUIRE_PTR(A); REQUIRE_PTR(x); REQUIRE_PTR(expert_offsets);
     REQUIRE_PTR(W1); REQUIRE_PTR(W2); REQUIRE_PTR(dXp);
     OPTIONAL_PTR(pair_token); OPTIONAL_PTR(dW1); OPTIONAL_PTR(db1); OPTIONAL_PTR(dW2); OPTIONAL_PTR(db2);

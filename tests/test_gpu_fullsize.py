@@ -1,0 +1,74 @@
+"""Full-size parity (configs 2-5) in the launch configuration the benchmark times: per-pair buffers sized
+from the pair count (not T*E), one context, forward then backward.  Whole-layer comparison where the oracle
+can afford it (late, sparse temperatures), otherwise the oracle on sampled tokens and on whole experts."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2112_14397_amd import binding as B
+from paper_2112_14397_amd import synth
+import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+_inputs = {}
+
+
+def inputs(name):
+    if name not in _inputs:
+        _inputs.clear()                      # one full-size input set at a time (host memory)
+        _inputs[name] = synth.make_layer_inputs(synth.CONFIGS[name])
+    return _inputs[name]
+
+
+def bench_like_layer(inp, tau):
+    """P_cap as the benchmark sizes it: pair count of a probe pass + 2 % + 256."""
+    cfg = inp.cfg
+    probe = H.GpuLayer(inp, P_cap=cfg.T * cfg.E, backward=False)
+    shape8 = B.make_shape(cfg.T, cfg.d, cfg.E, 8, cfg.dtype, cfg.act, cfg.T * cfg.E)
+    b = probe.buf
+    B.evomoe_dts_gate(probe.ctx, shape8, probe.x, probe.params.Wg, probe.params.bg, probe.noise, float(tau),
+                      float(cfg.threshold), b.gprime, None, b.mask_bits, b.counts, b.k)
+    P = int(b.k.sum().item())
+    del probe, b
+    torch.cuda.empty_cache()
+    return H.GpuLayer(inp, P_cap=int(P * 1.02) + 256, backward=True), P
+
+
+SAMPLED = [("gpt", 0), ("gpt", 3), ("roberta", 0), ("roberta", -1), ("mt", 0), ("large", 3), ("large", -1)]
+
+
+@pytest.mark.parametrize("name,ti", SAMPLED, ids=[f"{n}-tau{i}" for n, i in SAMPLED])
+def test_full_size_sampled(name, ti):
+    inp = inputs(name)
+    cfg = inp.cfg
+    tau = cfg.taus[ti]
+    gl, P = bench_like_layer(inp, tau)
+    rep = {}
+    worst = H.compare_full_size_sampled(gl, inp, tau, cfg.threshold, report=rep)
+    assert rep["P"] == P
+    print(f"\n{name} tau={tau:.3f}: {rep}  worst err/bound " + " ".join(f"{k}={v:.2f}" for k, v in worst.items()))
+
+
+WHOLE = [("gpt", -1), ("gpt", 3), ("roberta", -1), ("mt", 0)]
+
+
+@pytest.mark.parametrize("name,ti", WHOLE, ids=[f"{n}-tau{i}" for n, i in WHOLE])
+def test_full_size_whole_layer(name, ti):
+    """Late in the sweep the layer is sparse enough for the oracle to run all of it: every output of every
+    stage, forward and backward, element by element."""
+    inp = inputs(name)
+    cfg = inp.cfg
+    tau = cfg.taus[ti]
+    gl, P = bench_like_layer(inp, tau)
+    rep = {}
+    fwd, P2, _, _ = H.compare_forward(gl, inp, tau, cfg.threshold, report=rep)
+    assert P2 == P
+    # dx, dWg and dbg sit behind dG = <dy, O>, which nearly cancels for some pairs: the rounding of the
+    # bf16-stored O reaches them amplified (a handful of the T*d elements of dx pass 1x the bound).  End to
+    # end they are held to twice the tolerance, and the two stages that produce them to the plain tolerance
+    # on the inputs the kernels actually had.
+    _, worst = H.compare_backward(gl, inp, fwd, tau, slack={"dx": 2.0, "dWg": 2.0, "dbg": 2.0})
+    stage = H.compare_backward_stages(gl, inp, fwd, tau)
+    print(f"\n{name} tau={tau:.3f}: {rep}  worst err/bound " + " ".join(f"{k}={v:.2f}" for k, v in worst.items())
+          + "  stages: " + " ".join(f"{k}={v:.2f}" for k, v in stage.items()))
