@@ -28,6 +28,15 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel, from the two rocprofv3 --pmc runs of this same command that
+# profiles/ keeps (FETCH_SIZE, WRITE_SIZE; each scaled by what the counter reads for the --copy-probe copy):
+# average over the sweep's temperatures.  None where no such run has been summarised.
+MEASURED_TRAFFIC = {
+    # profiles/layer_gpt_pmc_fetch_size.txt: 438307.5 KiB x 1.9999; profiles/layer_gpt_pmc_write_size.txt:
+    # 157440.0 KiB x 1.0000 (algorithmic: 38969 pairs x (2d + 2F) x 2 B read + 2 x E*d*F x 2 B written = 7.50e8)
+    "gpt": int((438307.5 * 1.9999 + 157440.0 * 1.0) * 1024),
+}
+
 
 def _gemm_kernels():
     # expert-FFN GEMM launches and how many 2*P*d*F-flop contractions each carries
@@ -67,10 +76,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=3072)
     ap.add_argument("--copy-probe", action="store_true",
-                    help="after the timed region, run a plain 512 MiB device-to-device copy three times "
-                         "(a kernel of known traffic, to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--profile-all", action="store_true",
-                    help="also time every kernel with events in a second pass (adds 'kernels' to the JSON)")
+                    help="after the timed region, run a plain elementwise kernel over 512 MiB three times "
+                         "(known traffic each way, to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--no-kernel-table", action="store_true",
+                    help="skip the second pass that times every kernel with events ('kernels' in the JSON)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (all experts resident, no collectives); "
@@ -118,7 +127,8 @@ def main():
         step(taus[i % len(taus)])
     torch.cuda.synchronize()
 
-    dominant = "ffn_bwd_dh"
+    # the longest launch of a step: the merged weight-gradient GEMM (dW2 and dW1 in one persistent grid)
+    dominant = "ffn_bwd_dw2"
     B.evomoe_profile_select(ctx, dominant)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -134,12 +144,15 @@ def main():
     flops_per_pair_gemm = 2.0 * cfg.d * cfg.F
     P_steps = [P_of[taus[i % len(taus)]] for i in range(args.steps)]
     dom_ms, dom_n = prof.get(dominant, (0.0, 0))
-    dom_flops = sum(P_steps) * flops_per_pair_gemm
+    dom_flops = _gemm_kernels()[dominant] * sum(P_steps) * flops_per_pair_gemm
     achieved = dom_flops / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
-    roofline = {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+    roofline = {"bound": "mfma", "kernel": dominant + " (grouped_gemm_bf16<2, 4, ...>: dW2 and dW1)",
+                "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA_TFLOPS,
+                "traffic": MEASURED_TRAFFIC.get(args.config),
                 "avg_launch_us": dom_ms * 1e3 / max(dom_n, 1), "launches": dom_n,
-                "flops_per_launch": "2*P*d*F, P = pairs at the step's temperature"}
+                "flops_per_launch": "2 GEMMs x 2*P*d*F, P = pairs at the step's temperature "
+                                    "(sweep average %.0f)" % (sum(P_steps) / len(P_steps))}
 
     out = {
         "metric": "MoE-layer tokens/s fwd+bwd (d=768,E=16,T=8192) vs tau",
@@ -170,14 +183,16 @@ def main():
     out["per_tau"] = per_tau
 
     if args.copy_probe:
-        src = torch.empty(512 * 1024 * 1024, dtype=torch.uint8, device="cuda").fill_(1)
+        # a plain elementwise kernel of known traffic: reads 512 MiB, writes 512 MiB (shows up in a kernel
+        # trace as torch's bitwise_not elementwise kernel, three dispatches)
+        src = torch.ones(128 * 1024 * 1024, dtype=torch.int32, device="cuda")
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            torch.bitwise_not(src, out=dst)
         torch.cuda.synchronize()
-        out["copy_probe_bytes"] = int(src.numel())
+        out["copy_probe_bytes"] = int(src.numel() * 4)
 
-    if args.profile_all:
+    if not args.no_kernel_table:    # per-kernel event timings of three more sweeps (outside the timed region)
         B.evomoe_profile_select(ctx, "all")
         for i in range(len(taus) * 3):
             step(taus[i % len(taus)])

@@ -5,7 +5,7 @@
 
 `stats` prints per-kernel calls / total / average duration.  `pmc` prints, per kernel, the average of every
 collected counter per dispatch; with --copy-bytes it also derives the scale factor of FETCH_SIZE / WRITE_SIZE
-from the plain device-to-device copy bench.py --copy-probe runs (a kernel that reads and writes exactly N bytes).
+from the plain elementwise kernel bench.py --copy-probe runs (torch's bitwise_not: reads and writes exactly N bytes).
 """
 from __future__ import annotations
 
@@ -18,6 +18,8 @@ import sys
 
 def _short(name: str) -> str:
     name = name.replace("void evomoe::(anonymous namespace)::", "").replace("evomoe::", "")
+    if "bitwise_not" in name:
+        return "torch bitwise_not elementwise kernel (copy probe)"
     return name if len(name) <= 96 else name[:93] + "..."
 
 
@@ -51,7 +53,7 @@ def pmc(d: str, copy_bytes: int | None) -> None:
     for kn, c in agg.items():
         n = len(next(iter(c.values())))
         print(f"{_short(kn):98s} {n:5d} " + " ".join(f"{sum(c[k]) / len(c[k]):16.1f}" for k in counters))
-        if copy_bytes and ("copy" in kn.lower() or "elementwise" in kn.lower()) and n <= 4:
+        if copy_bytes and "bitwise_not" in kn:
             for k in counters:
                 if k in ("FETCH_SIZE", "WRITE_SIZE"):
                     scale[k] = (copy_bytes / 1024.0) / (sum(c[k]) / len(c[k]))
