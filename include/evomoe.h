@@ -73,7 +73,7 @@ typedef struct {
 
 /* Create / destroy a context bound to one HIP stream (hipStream_t passed as void*; NULL = default
  * stream) on the current device.  The context owns only small device scratch (per-block expert
- * histograms, a status word); it may grow that scratch, with a device allocation, the first time a
+ * histograms, a status word and, for a bf16 layer, W_g split into three bf16 planes); it may grow that scratch, with a device allocation, the first time a
  * larger T is seen.  Not thread-safe: one context per host thread/stream. */
 evomoe_status evomoe_create(evomoe_ctx** ctx_out, void* hip_stream);
 evomoe_status evomoe_destroy(evomoe_ctx* ctx);
