@@ -64,11 +64,10 @@ def test_full_size_whole_layer(name, ti):
     rep = {}
     fwd, P2, _, _ = H.compare_forward(gl, inp, tau, cfg.threshold, report=rep)
     assert P2 == P
-    # dx, dWg and dbg sit behind dG = <dy, O>, which nearly cancels for some pairs: the rounding of the
-    # bf16-stored O reaches them amplified (a handful of the T*d elements of dx pass 1x the bound).  End to
-    # end they are held to twice the tolerance, and the two stages that produce them to the plain tolerance
-    # on the inputs the kernels actually had.
-    _, worst = H.compare_backward(gl, inp, fwd, tau, slack={"dx": 2.0, "dWg": 2.0, "dbg": 2.0})
+    # outputs behind several bf16-stored intermediates are held to twice the tolerance end to end
+    # (gpu_harness.CHAIN_SLACK), and the two stages that produce dx, dWg, dbg to the plain tolerance on the
+    # inputs the kernels actually had
+    _, worst = H.compare_backward(gl, inp, fwd, tau, slack=H.CHAIN_SLACK if cfg.dtype == "bf16" else None)
     stage = H.compare_backward_stages(gl, inp, fwd, tau)
     print(f"\n{name} tau={tau:.3f}: {rep}  worst err/bound " + " ".join(f"{k}={v:.2f}" for k, v in worst.items())
           + "  stages: " + " ".join(f"{k}={v:.2f}" for k, v in stage.items()))
