@@ -105,6 +105,12 @@ __device__ __forceinline__ float act_grad_fast(float h, int act) {
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
+// Eight floats -> bf16, one 16-byte store with the streaming (non-temporal) hint: the outputs are far larger
+// than the L2 and are not read again by this kernel, while the operand panels they would evict are.
+__device__ __forceinline__ void store_out(bf16_t* p, const float* in) {
+    u32x4 v = {pack_bf16x2(in[0], in[1]), pack_bf16x2(in[2], in[3]), pack_bf16x2(in[4], in[5]), pack_bf16x2(in[6], in[7])};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
+}
 // The global address is a wave-uniform base (an SGPR pair) plus a 32-bit unsigned byte offset per lane.
 __device__ __forceinline__ void load_to_lds(const unsigned char* base, uint32_t voff, const unsigned char* lds_wave_base) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
@@ -516,7 +522,8 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
                 }
             // this wave's LDS writes are done -- and so are the loads issued above: waiting for them one by
             // one between the stores below would also wait for those stores (one counter covers both)
-            __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0) lgkmcnt(0)
+            if (pass == 0 || EPI == E_ACTGRAD) __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0) lgkmcnt(0)
+            else __builtin_amdgcn_s_waitcnt(0xc07f);     // lgkmcnt(0) only: the first pass's stores stay in flight
             __builtin_amdgcn_wave_barrier();
 #pragma unroll EPI_UNROLL
             for (int it = 0; it < NIT; ++it) {
@@ -537,7 +544,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
 #pragma unroll
                         for (int q = 0; q < 8; ++q) v[q] += old[q];
                     }
-                    if (ok) Elem<bf16_t>::store_vec(dst, v);
+                    if (ok) store_out(dst, v);
                 } else {
                     const bool ok = col < p.N && trow < rows;
                     const int64_t grow = (int64_t)(row0 + min(trow, rows - 1));
@@ -558,7 +565,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
                             for (int q = 0; q < 8; ++q) v[q] *= act_grad_fast(h[q], EVOMOE_GELU_ERF);
                         }
                     }
-                    if (ok) Elem<bf16_t>::store_vec(p.out1 + grow * p.N + col_c, v);
+                    if (ok) store_out(p.out1 + grow * p.N + col_c, v);
                     if (EPI == E_HA) {
                         float a[8];
                         if (p.act == EVOMOE_RELU) {
@@ -568,7 +575,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
 #pragma unroll
                             for (int q = 0; q < 8; ++q) a[q] = act_fwd_fast(v[q], EVOMOE_GELU_ERF);
                         }
-                        if (ok) Elem<bf16_t>::store_vec(p.out2 + grow * p.N + col_c, a);
+                        if (ok) store_out(p.out2 + grow * p.N + col_c, a);
                     }
                 }
             }
