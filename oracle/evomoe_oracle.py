@@ -27,7 +27,9 @@ Pins (tests/test_oracle_*.py, all run without a GPU): the paper's worked gate
 example, the E=2 sigmoid closed form, the dense (tau->inf, c=0) and top-1
 (tau->0) limits, textbook values of Phi, a literal per-token brute force of
 Algorithm 1, torch-CPU float64 autograd of an all-experts formulation, and
-central finite differences.  No function here is "parity unpinned".
+central finite differences; the balance loss and its gradient by a closed form,
+finite differences and autograd; the schedule by the paper's quoted step counts.
+No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -303,17 +305,22 @@ def dispatch_bwd(dXp, tok_off, tok_rows, T):
     return dx
 
 
-def dts_gate_bwd(dG_pairs, pair_token, pair_expert, gprime, tau, x, Wg):
+def dts_gate_bwd(dG_pairs, pair_token, pair_expert, gprime, tau, x, Wg, dgprime_coef=None):
     """Backward of G = mask * softmax(z / tau), z = x W_g + b_g + zeta.
 
     dG_si is dG_pairs at selected pairs and 0 elsewhere.  Softmax backward:
     dz_sj = (g'_sj / tau) * (dG_sj - sum_i dG_si g'_si).  Unselected columns
     still receive gradient through the normaliser.
+    dgprime_coef [E], optional: a gradient with respect to g'_si that is the
+    same for every token (the balance loss's, see balance_loss_grad); it is
+    added to dG_si for every (s, i), selected or not.
     Returns dz, dWg, dbg and the gate's contribution to dx.
     """
     T, E = gprime.shape
     dG = np.zeros((T, E), F64)
     dG[pair_token, pair_expert] = dG_pairs
+    if dgprime_coef is not None:
+        dG = dG + np.asarray(dgprime_coef, F64)[None, :]
     inner = (dG * gprime).sum(axis=1, keepdims=True)
     dz = gprime * (dG - inner) / F64(tau)
     dWg = np.asarray(x, F64).T @ dz
@@ -353,3 +360,45 @@ def balance_loss(gate: GateOut, alpha=0.1):
     """alpha * N * sum_i (count_i / |B|^2) * sum_s g'_si."""
     T, E = gate.gprime.shape
     return F64(alpha) * E * float((gate.counts / F64(T) ** 2 * gate.gprime.sum(axis=0)).sum())
+
+
+def balance_loss_grad(gate: GateOut, alpha=0.1):
+    """d L_balance / d g'_si = alpha * N * count_i / |B|^2 for every token s.
+
+    The count is an indicator sum (Eq. "balance_loss"): piecewise constant in
+    the gate's parameters, so it is a constant of the differentiation, as in
+    the Switch-style loss the paper refers to.  Returns the [E] coefficient
+    vector that dts_gate_bwd takes as dgprime_coef."""
+    T, E = gate.gprime.shape
+    return F64(alpha) * E * gate.counts.astype(F64) / F64(T) ** 2
+
+
+# ---------------------------------------------------------------------------
+# Training phases (Algorithm 1's loop bounds; Algorithm 2's T_D switch; the
+# Sparsity Scheduler paragraph; "we decay temperature from max_value to
+# min_value in the first ... iterations and switch to Top1 then")
+# ---------------------------------------------------------------------------
+
+@dataclass
+class Phase:
+    stage: int      # 1 = expert-diversify (one shared expert, no gate), 2 = gate-sparsify
+    top1: bool      # stage 2 only: Algorithm 2's else-branch
+    tau: float      # stage 2 only
+
+
+def schedule(iteration, T_S, T_D, tau_hi=2.0, tau_lo=0.3) -> Phase:
+    """Phase of training iteration `iteration` (0-based).
+
+    Iterations [0, T_S) train the shared expert.  The next T_D iterations run
+    the threshold gate while tau goes from tau_hi to tau_lo, both end points
+    reached (a linear ramp: the paper gives the end points and the duration
+    only).  From T_S + T_D on the gate is Top-1 at tau_lo.  T_D counts from the
+    start of stage 2 (Algorithm 2 compares it with the current iteration; the
+    experiments quote it as the number of steps after the first stage)."""
+    if iteration < T_S:
+        return Phase(1, False, float("nan"))
+    j = iteration - T_S
+    if j < T_D:
+        tau = tau_hi if T_D == 1 else tau_hi - (tau_hi - tau_lo) * (j / F64(T_D - 1))
+        return Phase(2, False, float(tau))
+    return Phase(2, True, float(tau_lo))

@@ -133,3 +133,95 @@ def test_unrouted_expert_gets_zero_weight_gradient():
         assert not bwd.ffn.dW1[i].any() and not bwd.ffn.dW2[i].any()
         assert not bwd.ffn.db1[i].any() and not bwd.ffn.db2[i].any()
     assert bwd.ffn.dW1[0].any() and bwd.ffn.dW2[2].any()
+
+
+# ---------------------------------------------------------------------------------------------
+# Balance loss (Eq. balance_loss), its gradient, and the training-phase schedule
+# ---------------------------------------------------------------------------------------------
+
+def test_balance_loss_closed_forms():
+    """Uniform routing: every token selects every expert and g' = 1/N -> L = alpha*N*sum_i (T/T^2)(T/N) = alpha*N.
+    One-hot routing to a single expert with g' = one-hot -> count = (T,0,..), sum g' = (T,0,..) -> L = alpha*N."""
+    T, E, alpha = 12, 4, 0.1
+    gp = np.full((T, E), 1.0 / E)
+    g = orc.GateOut(gp, gp.copy(), np.ones((T, E), bool), np.full(E, T), np.full(T, E), 0)
+    assert orc.balance_loss(g, alpha) == pytest.approx(alpha * E)
+    oh = np.zeros((T, E)); oh[:, 2] = 1.0
+    g = orc.GateOut(oh, oh.copy(), oh.astype(bool), np.array([0, 0, T, 0]), np.ones(T, int), 0)
+    assert orc.balance_loss(g, alpha) == pytest.approx(alpha * E)
+    # perfectly balanced top-1 routing with uniform probabilities is the minimum alpha (Switch-style loss)
+    m = np.zeros((T, E), bool); m[np.arange(T), np.arange(T) % E] = True
+    g = orc.GateOut(gp, np.where(m, gp, 0), m, np.full(E, T // E), np.ones(T, int), 0)
+    assert orc.balance_loss(g, alpha) == pytest.approx(alpha)
+    np.testing.assert_allclose(orc.balance_loss_grad(g, alpha), alpha * E * (T // E) / T ** 2)
+
+
+def test_balance_loss_gradient_matches_finite_differences_and_autograd():
+    cfg, inp = _case(T=9, d=5, E=4)
+    tau, c, alpha = 0.8, 0.15, 0.1
+    gate = orc.dts_gate(inp.x, inp.Wg, inp.bg, inp.noise, tau, c)
+    dp = orc.dispatch(gate.mask, gate.G)
+    coef = orc.balance_loss_grad(gate, alpha)
+    zero = np.zeros(len(dp.pair_token))
+    dz, dWg, dbg, dx_g = orc.dts_gate_bwd(zero, dp.pair_token, dp.pair_expert, gate.gprime, tau, inp.x, inp.Wg,
+                                          dgprime_coef=coef)
+
+    def loss(Wg=inp.Wg, bg=inp.bg, x=inp.x):
+        g = orc.dts_gate(x, Wg, bg, inp.noise, tau, c, mask_override=gate.mask)     # counts held constant
+        return orc.balance_loss(g, alpha)
+
+    h = 1e-6
+    for (i, j) in ((0, 0), (3, 2), (4, 3)):
+        Wp, Wm = inp.Wg.astype(np.float64).copy(), inp.Wg.astype(np.float64).copy()
+        Wp[i, j] += h; Wm[i, j] -= h
+        assert (loss(Wg=Wp) - loss(Wg=Wm)) / (2 * h) == pytest.approx(dWg[i, j], rel=1e-5, abs=1e-10)
+    for j in range(cfg.E):
+        bp, bm = inp.bg.astype(np.float64).copy(), inp.bg.astype(np.float64).copy()
+        bp[j] += h; bm[j] -= h
+        assert (loss(bg=bp) - loss(bg=bm)) / (2 * h) == pytest.approx(dbg[j], rel=1e-5, abs=1e-10)
+    xp, xm = inp.x.astype(np.float64).copy(), inp.x.astype(np.float64).copy()
+    xp[2, 1] += h; xm[2, 1] -= h
+    assert (loss(x=xp) - loss(x=xm)) / (2 * h) == pytest.approx(dx_g[2, 1], rel=1e-5, abs=1e-10)
+
+    # autograd of the same loss written with torch ops
+    t = lambda a: torch.tensor(np.asarray(a, np.float64), requires_grad=True)
+    x, Wg, bg = t(inp.x), t(inp.Wg), t(inp.bg)
+    gp = torch.softmax((x @ Wg + bg + torch.tensor(inp.noise.astype(np.float64))) / tau, dim=1)
+    counts = torch.tensor(gate.counts.astype(np.float64))
+    L = alpha * cfg.E * (counts / cfg.T ** 2 * gp.sum(dim=0)).sum()
+    L.backward()
+    assert float(L.detach()) == pytest.approx(orc.balance_loss(gate, alpha))
+    np.testing.assert_allclose(dWg, Wg.grad.numpy(), rtol=1e-10, atol=1e-14)
+    np.testing.assert_allclose(dbg, bg.grad.numpy(), rtol=1e-10, atol=1e-14)
+    np.testing.assert_allclose(dx_g, x.grad.numpy(), rtol=1e-10, atol=1e-14)
+
+
+def test_dense_coefficient_adds_to_pair_gradients():
+    """Linearity: gate backward of (pair gradients + dense coefficients) = sum of the two backward passes."""
+    cfg, inp = _case()
+    tau, c = 1.0, 0.15
+    gate = orc.dts_gate(inp.x, inp.Wg, inp.bg, inp.noise, tau, c)
+    dp = orc.dispatch(gate.mask, gate.G)
+    rng = np.random.default_rng(5)
+    dGp, coef = rng.standard_normal(len(dp.pair_token)), rng.standard_normal(cfg.E)
+    a = orc.dts_gate_bwd(dGp, dp.pair_token, dp.pair_expert, gate.gprime, tau, inp.x, inp.Wg)
+    b = orc.dts_gate_bwd(0 * dGp, dp.pair_token, dp.pair_expert, gate.gprime, tau, inp.x, inp.Wg, dgprime_coef=coef)
+    ab = orc.dts_gate_bwd(dGp, dp.pair_token, dp.pair_expert, gate.gprime, tau, inp.x, inp.Wg, dgprime_coef=coef)
+    for u, v, w in zip(a, b, ab):
+        np.testing.assert_allclose(u + v, w, rtol=1e-12, atol=1e-14)
+
+
+def test_schedule_follows_the_papers_step_counts():
+    """Experimental Setup: first 5k steps expert-diversify, following 5k steps anneal 2.0 -> 0.3; Top-1 after."""
+    T_S, T_D = 5000, 5000
+    assert orc.schedule(0, T_S, T_D).stage == 1 and orc.schedule(4999, T_S, T_D).stage == 1
+    first, last = orc.schedule(5000, T_S, T_D), orc.schedule(9999, T_S, T_D)
+    assert (first.stage, first.top1, first.tau) == (2, False, 2.0)
+    assert (last.stage, last.top1) == (2, False) and last.tau == pytest.approx(0.3)
+    after = orc.schedule(10000, T_S, T_D)
+    assert (after.stage, after.top1) == (2, True) and after.tau == pytest.approx(0.3)
+    taus = [orc.schedule(i, T_S, T_D).tau for i in range(5000, 10000)]
+    assert all(a > b for a, b in zip(taus, taus[1:]))                       # strictly annealing
+    assert np.allclose(np.diff(taus), np.diff(taus)[0])                     # evenly: a linear ramp
+    assert [round(orc.schedule(i, 0, 6).tau, 6) for i in range(6)] == [round(t, 6) for t in synth.linear_tau_schedule(6)]
+    assert orc.schedule(7, 0, 1).top1 and orc.schedule(0, 0, 1).tau == 2.0
