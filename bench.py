@@ -44,7 +44,7 @@ def _gemm_kernels():
     return {"ffn_gemm1": 1, "ffn_gemm2": 1, "ffn_bwd_dh": 1, "ffn_bwd_dx": 1, "ffn_bwd_dw2": 2}
 
 
-def cpu_baseline(cfg, inp, n_tokens, taus):
+def cpu_baseline(cfg, inp, n_tokens, taus, top1=False):
     """The oracle as it stands, timed on the host cores on the first n_tokens tokens over the sweep."""
     import numpy as np
     from oracle import evomoe_oracle as orc
@@ -57,9 +57,12 @@ def cpu_baseline(cfg, inp, n_tokens, taus):
     t0 = time.perf_counter()
     pairs = 0
     for tau in taus:
+        override = orc.top1_gate(x, inp.Wg, inp.bg, noise, tau).mask if top1 else None
         fwd = orc.moe_layer_forward(x, inp.Wg, inp.bg, noise, tau, cfg.threshold, inp.W1, inp.b1,
-                                    inp.W2, inp.b2, cfg.act)
+                                    inp.W2, inp.b2, cfg.act, mask_override=override)
         orc.moe_layer_backward(fwd, dy, x, inp.Wg, tau, inp.W1, inp.W2, cfg.act)
+        if top1:
+            orc.balance_loss(fwd.gate, 0.1)
         pairs += int(fwd.disp.expert_offsets[-1])
     dt = time.perf_counter() - t0
     return {"value": n_tokens * len(taus) / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
@@ -74,6 +77,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--config", default="gpt")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mode", choices=("sweep", "top1"), default="sweep",
+                    help="sweep: the dense-to-sparse temperature sweep with the threshold gate (headline metric); "
+                         "top1: the steady state after the sweep -- Top-1 gate at the final temperature, P = T, "
+                         "with the balance loss (alpha = 0.1) in the backward")
+    ap.add_argument("--recompute", action="store_true",
+                    help="backward recomputes the expert activations instead of reading the forward's")
     ap.add_argument("--cpu-tokens", type=int, default=3072)
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region, run a plain elementwise kernel over 512 MiB three times "
@@ -103,25 +112,33 @@ def main():
                            W2=dev(inp.W2, dt), b2=dev(inp.b2))
     ctx = B.Context()
     taus = list(cfg.taus)
+    top1 = args.mode == "top1"
+    if top1:
+        taus = [taus[-1]]
+    alpha = 0.1 if top1 else None
 
     # size the per-pair buffers from the sweep's largest P (one untimed gate+dispatch per temperature)
     probe_shape = B.make_shape(cfg.T, cfg.d, cfg.E, 8, cfg.dtype, cfg.act, cfg.T * cfg.E)
     pb = B.LayerBuffers(probe_shape, backward=False)
     P_of = {}
     for tau in taus:
-        B.evomoe_dts_gate(ctx, probe_shape, x, params.Wg, params.bg, noise, tau, cfg.threshold, pb.gprime, None,
-                          pb.mask_bits, pb.counts, pb.k)
+        if top1:
+            B.evomoe_dts_gate_top1(ctx, probe_shape, x, params.Wg, params.bg, noise, tau, pb.gprime, None,
+                                   pb.mask_bits, pb.counts, pb.k)
+        else:
+            B.evomoe_dts_gate(ctx, probe_shape, x, params.Wg, params.bg, noise, tau, cfg.threshold, pb.gprime, None,
+                              pb.mask_bits, pb.counts, pb.k)
         B.evomoe_dispatch(ctx, probe_shape, pb.mask_bits, pb.gprime, pb.expert_offsets, pb.pair_token,
                           pb.pair_gate, pb.tok_off, pb.tok_rows, pb.num_pairs)
         P_of[tau] = B.evomoe_num_pairs(ctx, pb.num_pairs)
     del pb
     P_cap = int(max(P_of.values()) * 1.02) + 256
     shape = B.make_shape(cfg.T, cfg.d, cfg.E, cfg.F, cfg.dtype, cfg.act, P_cap)
-    buf = B.LayerBuffers(shape, backward=True)
+    buf = B.LayerBuffers(shape, backward=True, recompute=args.recompute)
 
     def step(tau):
-        B.layer_forward(ctx, buf, params, x, noise, tau, cfg.threshold, write_gate_w=False)
-        B.layer_backward(ctx, buf, params, x, dy, tau)
+        B.layer_forward(ctx, buf, params, x, noise, tau, cfg.threshold, write_gate_w=False, top1=top1)
+        B.layer_backward(ctx, buf, params, x, dy, tau, balance_alpha=alpha, recompute=args.recompute)
 
     for i in range(args.warmup):
         step(taus[i % len(taus)])
@@ -155,12 +172,15 @@ def main():
                                     "(sweep average %.0f)" % (sum(P_steps) / len(P_steps))}
 
     out = {
-        "metric": "MoE-layer tokens/s fwd+bwd (d=768,E=16,T=8192) vs tau",
+        "metric": "MoE-layer tokens/s fwd+bwd (d=768,E=16,T=8192) vs tau" if not top1 else
+                  "MoE-layer tokens/s fwd+bwd (d=768,E=16,T=8192), Top-1 steady state",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} F={cfg.F} {cfg.act} "
-                               f"c={cfg.threshold}, tau sweep {[round(t, 3) for t in taus]} (one tau per step, cyclic)",
+                               + (f"c={cfg.threshold}, tau sweep {[round(t, 3) for t in taus]} (one tau per step, cyclic)"
+                                  if not top1 else f"Top-1 gate at tau={taus[0]:.3f}, balance loss alpha=0.1")
+                               + (", backward recomputes H and A" if args.recompute else ""),
                    "pairs_per_tau": {f"{t:.3f}": P_of[t] for t in taus}, "P_cap": P_cap},
         "layer_tflops": 6.0 * flops_per_pair_gemm * sum(P_steps) / elapsed / 1e12,
         "roofline": roofline,
@@ -208,7 +228,7 @@ def main():
         out["kernels"] = ks
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, inp, min(args.cpu_tokens, cfg.T), taus)
+        out["cpu_baseline"] = cpu_baseline(cfg, inp, min(args.cpu_tokens, cfg.T), taus, top1=top1)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))

@@ -97,6 +97,27 @@ evomoe_status evomoe_dts_gate(evomoe_ctx* ctx, const evomoe_shape* shape,
                               float* gprime, float* gate_w, uint64_t* mask_bits,
                               int32_t* counts, int32_t* k_per_token);
 
+/* Top-1 branch of the DTS gate (Algorithm 2, else-branch: iterations >= T_D; "switch to Top1" in the
+ * temperature-scheduler study).  Same inputs and outputs as evomoe_dts_gate without a threshold: every
+ * token selects its arg-max expert (lowest index on ties) with weight g' of that expert, not renormalised,
+ * so k_s = 1 and P = T.  Every later step (dispatch ... gate backward) is the same call as for the
+ * threshold branch. */
+evomoe_status evomoe_dts_gate_top1(evomoe_ctx* ctx, const evomoe_shape* shape,
+                                   const void* x, const float* Wg, const float* bg, const float* noise,
+                                   float tau,
+                                   float* gprime, float* gate_w, uint64_t* mask_bits,
+                                   int32_t* counts, int32_t* k_per_token);
+
+/* Balance loss (Eq. balance_loss):  L = alpha * N * sum_i (count_i / T^2) * sum_s g'_si,
+ * and its gradient with respect to g'_si, which is the same for every token: coef_i = alpha * N * count_i / T^2
+ * (the indicator count is a constant of the differentiation).
+ *   in : gprime [T,E] f32, counts [E] i32 (both as written by the gate), alpha.
+ *   out: loss [1] f32 (device), dgprime_coef [E] f32 (device; may be NULL).
+ * Deterministic (fixed summation order). */
+evomoe_status evomoe_balance_loss(evomoe_ctx* ctx, const evomoe_shape* shape,
+                                  const float* gprime, const int32_t* counts, float alpha,
+                                  float* loss, float* dgprime_coef);
+
 /* Dispatch (Algorithm 1: the loop over id in id_s, turned into a permutation).  Stable counting
  * sort of the selected pairs: expert-major, token-ascending.
  *   in : mask_bits [T]; scores [T,E] f32 (g' or gate_w: only selected entries are read).
@@ -170,6 +191,43 @@ evomoe_status evomoe_dts_gate_bwd(evomoe_ctx* ctx, const evomoe_shape* shape,
                                   float* dWg, float* dbg, void* dx,
                                   void* workspace, size_t workspace_bytes);
 
+/* evomoe_dts_gate_bwd with one more gradient flowing into g': dgprime_coef [E] f32 (as written by
+ * evomoe_balance_loss), scaled by loss_scale, is added to dG_si for EVERY (s, i), selected or not, before the
+ * softmax backward.  dgprime_coef == NULL is evomoe_dts_gate_bwd. */
+evomoe_status evomoe_dts_gate_bwd_balance(evomoe_ctx* ctx, const evomoe_shape* shape,
+                                          const float* dG_pairs, const int32_t* tok_off, const int32_t* tok_rows,
+                                          const float* gprime, const uint64_t* mask_bits, float tau,
+                                          const void* x, const float* Wg,
+                                          const float* dgprime_coef, float loss_scale,
+                                          float* dWg, float* dbg, void* dx,
+                                          void* workspace, size_t workspace_bytes);
+
+/* Backward of the expert FFNs that keeps no activations between forward and backward (the single-GPU
+ * counterpart of the paper's MoE-aware recomputation, Implementation section): H and A are recomputed from x
+ * by the forward's first GEMM into the workspace, then the backward proceeds as evomoe_expert_ffn_bwd.
+ * Costs 14*d*F instead of 12*d*F flop per pair over forward + backward and saves 2*P_cap*F elements of
+ * resident activations.  Arguments as evomoe_expert_ffn_bwd without H and A, plus b1.
+ *   workspace: at least evomoe_workspace_bytes_recompute(shape) bytes. */
+size_t evomoe_workspace_bytes_recompute(const evomoe_shape* shape);
+evomoe_status evomoe_expert_ffn_bwd_recompute(evomoe_ctx* ctx, const evomoe_shape* shape,
+                                              const void* dO,
+                                              const void* x, const int32_t* pair_token, const int32_t* expert_offsets,
+                                              const void* W1, const float* b1, const void* W2,
+                                              void* dW1, float* db1, void* dW2, float* db2, void* dXp,
+                                              int accumulate, void* workspace, size_t workspace_bytes);
+
+/* Training phase of an iteration (host only, no device work; Algorithm 1's loop bounds, Algorithm 2's T_D
+ * switch, Sparsity Scheduler).  Iterations [0, T_S): stage 1 (one shared expert, this library is not
+ * involved).  The next T_D iterations: threshold gate, tau going linearly from tau_hi to tau_lo with both end
+ * points reached.  From T_S + T_D on: Top-1 gate at tau_lo. */
+typedef struct {
+    int32_t stage;   /* 1 = expert-diversify, 2 = gate-sparsify */
+    int32_t top1;    /* stage 2: 0 = evomoe_dts_gate, 1 = evomoe_dts_gate_top1 */
+    float tau;       /* stage 2 only (NaN in stage 1) */
+} evomoe_phase;
+evomoe_status evomoe_schedule(int64_t iteration, int64_t T_S, int64_t T_D, float tau_hi, float tau_lo,
+                              evomoe_phase* phase_out);
+
 /* Copies P to the host and reports a pending capacity overflow.  The only synchronising call. */
 evomoe_status evomoe_num_pairs(evomoe_ctx* ctx, const int64_t* num_pairs, int64_t* num_pairs_host);
 
@@ -184,6 +242,7 @@ typedef enum {
     EVOMOE_K_FFN_GEMM2, EVOMOE_K_COMBINE, EVOMOE_K_COMBINE_BWD, EVOMOE_K_FFN_BWD_DH,
     EVOMOE_K_FFN_BWD_DX, EVOMOE_K_FFN_BWD_DW2, EVOMOE_K_FFN_BWD_DW1, EVOMOE_K_FFN_BWD_DB,
     EVOMOE_K_DISPATCH_BWD, EVOMOE_K_GATE_BWD_DZ, EVOMOE_K_GATE_BWD_MAIN, EVOMOE_K_GATE_BWD_REDUCE,
+    EVOMOE_K_BALANCE_LOSS,
     EVOMOE_K_COUNT, EVOMOE_K_ALL = -2, EVOMOE_K_NONE = -1
 } evomoe_kernel_id;
 evomoe_status evomoe_profile_select(evomoe_ctx* ctx, int kernel_id);

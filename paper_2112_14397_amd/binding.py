@@ -25,11 +25,13 @@ ENTRY_POINTS = (
     "evomoe_dts_gate", "evomoe_dispatch", "evomoe_expert_ffn", "evomoe_combine",
     "evomoe_combine_bwd", "evomoe_expert_ffn_bwd", "evomoe_dispatch_bwd", "evomoe_dts_gate_bwd",
     "evomoe_num_pairs", "evomoe_profile_select", "evomoe_profile_read",
+    "evomoe_dts_gate_top1", "evomoe_balance_loss", "evomoe_dts_gate_bwd_balance",
+    "evomoe_workspace_bytes_recompute", "evomoe_expert_ffn_bwd_recompute", "evomoe_schedule",
 )
 
 KERNEL_IDS = ("gate", "dispatch_hist", "dispatch_scatter", "ffn_gemm1", "ffn_gemm2", "combine", "combine_bwd",
               "ffn_bwd_dh", "ffn_bwd_dx", "ffn_bwd_dw2", "ffn_bwd_dw1", "ffn_bwd_db", "dispatch_bwd",
-              "gate_bwd_dz", "gate_bwd_main", "gate_bwd_reduce")
+              "gate_bwd_dz", "gate_bwd_main", "gate_bwd_reduce", "balance_loss")
 EVOMOE_K_ALL, EVOMOE_K_NONE = -2, -1
 
 
@@ -38,6 +40,10 @@ class EvoMoEError(RuntimeError):
         self.status = status
         msg = lib().evomoe_status_string(status).decode()
         super().__init__(f"{where}: {msg} ({status})")
+
+
+class Phase(ctypes.Structure):
+    _fields_ = [("stage", ctypes.c_int32), ("top1", ctypes.c_int32), ("tau", ctypes.c_float)]
 
 
 class Shape(ctypes.Structure):
@@ -73,10 +79,17 @@ def lib() -> ctypes.CDLL:
         L.evomoe_dispatch_bwd.argtypes = [vp, sp] + [vp] * 4
         L.evomoe_dts_gate_bwd.argtypes = [vp, sp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, vp, sz]
         L.evomoe_num_pairs.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int64)]
+        L.evomoe_dts_gate_top1.argtypes = [vp, sp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
+        L.evomoe_balance_loss.argtypes = [vp, sp, vp, vp, f32, vp, vp]
+        L.evomoe_dts_gate_bwd_balance.argtypes = [vp, sp, vp, vp, vp, vp, vp, f32, vp, vp, vp, f32, vp, vp, vp, vp, sz]
+        L.evomoe_workspace_bytes_recompute.argtypes = [sp]
+        L.evomoe_workspace_bytes_recompute.restype = sz
+        L.evomoe_expert_ffn_bwd_recompute.argtypes = [vp, sp] + [vp] * 12 + [i32, vp, sz]
+        L.evomoe_schedule.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, f32, f32, ctypes.POINTER(Phase)]
         L.evomoe_profile_select.argtypes = [vp, i32]
         L.evomoe_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
         for n in ENTRY_POINTS:
-            if n not in ("evomoe_status_string", "evomoe_workspace_bytes"):
+            if n not in ("evomoe_status_string", "evomoe_workspace_bytes", "evomoe_workspace_bytes_recompute"):
                 getattr(L, n).restype = i32
         _lib = L
     return _lib
@@ -178,6 +191,45 @@ def evomoe_dts_gate_bwd(ctx, shape, dG_pairs, tok_off, tok_rows, gprime, mask_bi
          "evomoe_dts_gate_bwd")
 
 
+def evomoe_dts_gate_top1(ctx, shape, x, Wg, bg, noise, tau, gprime, gate_w, mask_bits, counts, k_per_token):
+    _chk(lib().evomoe_dts_gate_top1(ctx._h, ctypes.byref(shape), _p(x), _p(Wg), _p(bg), _p(noise), tau,
+                                    _p(gprime), _p(gate_w), _p(mask_bits), _p(counts), _p(k_per_token)),
+         "evomoe_dts_gate_top1")
+
+
+def evomoe_balance_loss(ctx, shape, gprime, counts, alpha, loss, dgprime_coef):
+    _chk(lib().evomoe_balance_loss(ctx._h, ctypes.byref(shape), _p(gprime), _p(counts), alpha, _p(loss),
+                                   _p(dgprime_coef)), "evomoe_balance_loss")
+
+
+def evomoe_dts_gate_bwd_balance(ctx, shape, dG_pairs, tok_off, tok_rows, gprime, mask_bits, tau, x, Wg,
+                                dgprime_coef, loss_scale, dWg, dbg, dx, workspace):
+    _chk(lib().evomoe_dts_gate_bwd_balance(ctx._h, ctypes.byref(shape), _p(dG_pairs), _p(tok_off), _p(tok_rows),
+                                           _p(gprime), _p(mask_bits), tau, _p(x), _p(Wg), _p(dgprime_coef),
+                                           loss_scale, _p(dWg), _p(dbg), _p(dx), _p(workspace),
+                                           workspace.numel() * workspace.element_size()),
+         "evomoe_dts_gate_bwd_balance")
+
+
+def evomoe_workspace_bytes_recompute(shape: Shape) -> int:
+    return int(lib().evomoe_workspace_bytes_recompute(ctypes.byref(shape)))
+
+
+def evomoe_expert_ffn_bwd_recompute(ctx, shape, dO, x, pair_token, expert_offsets, W1, b1, W2, dW1, db1, dW2, db2,
+                                    dXp, accumulate, workspace):
+    _chk(lib().evomoe_expert_ffn_bwd_recompute(ctx._h, ctypes.byref(shape), _p(dO), _p(x), _p(pair_token),
+                                               _p(expert_offsets), _p(W1), _p(b1), _p(W2), _p(dW1), _p(db1),
+                                               _p(dW2), _p(db2), _p(dXp), int(accumulate), _p(workspace),
+                                               workspace.numel() * workspace.element_size()),
+         "evomoe_expert_ffn_bwd_recompute")
+
+
+def evomoe_schedule(iteration, T_S, T_D, tau_hi=2.0, tau_lo=0.3) -> Phase:
+    ph = Phase()
+    _chk(lib().evomoe_schedule(iteration, T_S, T_D, tau_hi, tau_lo, ctypes.byref(ph)), "evomoe_schedule")
+    return ph
+
+
 def evomoe_num_pairs(ctx, num_pairs) -> int:
     out = ctypes.c_int64(0)
     _chk(lib().evomoe_num_pairs(ctx._h, _p(num_pairs), ctypes.byref(out)), "evomoe_num_pairs")
@@ -214,7 +266,7 @@ class LayerParams:
 class LayerBuffers:
     """Every output / saved tensor of one forward+backward pass, allocated once."""
 
-    def __init__(self, shape: Shape, device="cuda", backward=True):
+    def __init__(self, shape: Shape, device="cuda", backward=True, recompute=False):
         T, d, E, F, P = shape.T, shape.d, shape.E, shape.F, shape.P_cap
         dt = torch.bfloat16 if shape.dtype == EVOMOE_BF16 else torch.float32
         z = lambda *s, dtype=dt: torch.zeros(*s, dtype=dtype, device=device)
@@ -230,24 +282,43 @@ class LayerBuffers:
             self.dO = z(P, d); self.dG_pairs = z(P, dtype=f32); self.dXp = z(P, d); self.dx = z(T, d)
             self.dW1 = z(E, F, d); self.dW2 = z(E, d, F); self.db1 = z(E, F, dtype=f32); self.db2 = z(E, d, dtype=f32)
             self.dWg = z(d, E, dtype=f32); self.dbg = z(E, dtype=f32)
-            self.workspace = torch.empty(max(evomoe_workspace_bytes(shape), 256), dtype=torch.uint8, device=device)
+            nbytes = evomoe_workspace_bytes_recompute(shape) if recompute else evomoe_workspace_bytes(shape)
+            self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+            self.bal_loss = z(1, dtype=f32); self.bal_coef = z(E, dtype=f32)
 
 
-def layer_forward(ctx, b: LayerBuffers, p: LayerParams, x, noise, tau, threshold, write_gate_w=True):
+def layer_forward(ctx, b: LayerBuffers, p: LayerParams, x, noise, tau, threshold, write_gate_w=True, top1=False):
     s = b.shape
-    evomoe_dts_gate(ctx, s, x, p.Wg, p.bg, noise, tau, threshold, b.gprime, b.gate_w if write_gate_w else None,
-                    b.mask_bits, b.counts, b.k)
+    if top1:
+        evomoe_dts_gate_top1(ctx, s, x, p.Wg, p.bg, noise, tau, b.gprime, b.gate_w if write_gate_w else None,
+                             b.mask_bits, b.counts, b.k)
+    else:
+        evomoe_dts_gate(ctx, s, x, p.Wg, p.bg, noise, tau, threshold, b.gprime, b.gate_w if write_gate_w else None,
+                        b.mask_bits, b.counts, b.k)
     evomoe_dispatch(ctx, s, b.mask_bits, b.gprime, b.expert_offsets, b.pair_token, b.pair_gate, b.tok_off,
                     b.tok_rows, b.num_pairs)
     evomoe_expert_ffn(ctx, s, x, b.pair_token, b.expert_offsets, p.W1, p.b1, p.W2, p.b2, b.H, b.A, b.O)
     evomoe_combine(ctx, s, b.O, b.pair_gate, b.tok_off, b.tok_rows, b.y)
 
 
-def layer_backward(ctx, b: LayerBuffers, p: LayerParams, x, dy, tau, accumulate=False):
+def layer_backward(ctx, b: LayerBuffers, p: LayerParams, x, dy, tau, accumulate=False, balance_alpha=None,
+                   recompute=False):
+    """balance_alpha: also evaluate the balance loss and add its gradient in the gate backward (needs
+    b.bal_loss [1] f32 and b.bal_coef [E] f32).  recompute: the FFN backward recomputes H and A (needs
+    b.workspace of evomoe_workspace_bytes_recompute bytes); b.H and b.A are then not read."""
     s = b.shape
     evomoe_combine_bwd(ctx, s, dy, b.O, b.pair_gate, b.pair_token, b.expert_offsets, b.dO, b.dG_pairs)
-    evomoe_expert_ffn_bwd(ctx, s, b.dO, b.H, b.A, x, b.pair_token, b.expert_offsets, p.W1, p.W2,
-                          b.dW1, b.db1, b.dW2, b.db2, b.dXp, accumulate, b.workspace)
+    if recompute:
+        evomoe_expert_ffn_bwd_recompute(ctx, s, b.dO, x, b.pair_token, b.expert_offsets, p.W1, p.b1, p.W2,
+                                        b.dW1, b.db1, b.dW2, b.db2, b.dXp, accumulate, b.workspace)
+    else:
+        evomoe_expert_ffn_bwd(ctx, s, b.dO, b.H, b.A, x, b.pair_token, b.expert_offsets, p.W1, p.W2,
+                              b.dW1, b.db1, b.dW2, b.db2, b.dXp, accumulate, b.workspace)
     evomoe_dispatch_bwd(ctx, s, b.dXp, b.tok_off, b.tok_rows, b.dx)
-    evomoe_dts_gate_bwd(ctx, s, b.dG_pairs, b.tok_off, b.tok_rows, b.gprime, b.mask_bits, tau, x, p.Wg,
-                        b.dWg, b.dbg, b.dx, b.workspace)
+    if balance_alpha is not None:
+        evomoe_balance_loss(ctx, s, b.gprime, b.counts, float(balance_alpha), b.bal_loss, b.bal_coef)
+        evomoe_dts_gate_bwd_balance(ctx, s, b.dG_pairs, b.tok_off, b.tok_rows, b.gprime, b.mask_bits, tau, x, p.Wg,
+                                    b.bal_coef, 1.0, b.dWg, b.dbg, b.dx, b.workspace)
+    else:
+        evomoe_dts_gate_bwd(ctx, s, b.dG_pairs, b.tok_off, b.tok_rows, b.gprime, b.mask_bits, tau, x, p.Wg,
+                            b.dWg, b.dbg, b.dx, b.workspace)

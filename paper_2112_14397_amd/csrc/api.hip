@@ -170,6 +170,27 @@ evomoe_status evomoe_dts_gate(evomoe_ctx* ctx, const evomoe_shape* shape, const 
                                     mask_bits, counts, k_per_token));
 }
 
+evomoe_status evomoe_dts_gate_top1(evomoe_ctx* ctx, const evomoe_shape* shape, const void* x,
+                                   const float* Wg, const float* bg, const float* noise, float tau,
+                                   float* gprime, float* gate_w, uint64_t* mask_bits, int32_t* counts,
+                                   int32_t* k_per_token) {
+    // No score exceeds a threshold above 1, so every token takes the arg-max rule of the threshold gate
+    // (lowest index on ties): exactly Algorithm 2's Top-1 branch, with the un-renormalised weight g'.
+    return evomoe_dts_gate(ctx, shape, x, Wg, bg, noise, tau, 2.0f, gprime, gate_w, mask_bits, counts,
+                           k_per_token);
+}
+
+evomoe_status evomoe_balance_loss(evomoe_ctx* ctx, const evomoe_shape* shape, const float* gprime,
+                                  const int32_t* counts, float alpha, float* loss, float* dgprime_coef) {
+    CHECK_CTX_SHAPE();
+    REQUIRE_PTR(gprime); REQUIRE_PTR(counts);
+    if (!loss || (reinterpret_cast<uintptr_t>(loss) & 3u)) return EVOMOE_EINVAL;
+    if (dgprime_coef && (reinterpret_cast<uintptr_t>(dgprime_coef) & 3u)) return EVOMOE_EINVAL;
+    evomoe_status st = ensure_scratch(ctx->c, (size_t)balance_blocks(*shape) * shape->E);
+    if (st != EVOMOE_OK) return st;
+    return from_hip(launch_balance_loss(ctx->c, *shape, gprime, counts, alpha, loss, dgprime_coef));
+}
+
 evomoe_status evomoe_dispatch(evomoe_ctx* ctx, const evomoe_shape* shape, const uint64_t* mask_bits,
                               const float* scores, int32_t* expert_offsets, int32_t* pair_token,
                               float* pair_gate, int32_t* tok_off, int32_t* tok_rows,
@@ -253,6 +274,69 @@ evomoe_status evomoe_dts_gate_bwd(evomoe_ctx* ctx, const evomoe_shape* shape, co
         return EVOMOE_EWORKSPACE;
     return from_hip(launch_dts_gate_bwd(ctx->c, *shape, dG_pairs, tok_off, tok_rows, gprime, mask_bits,
                                         tau, x, Wg, dWg, dbg, dx, workspace));
+}
+
+evomoe_status evomoe_dts_gate_bwd_balance(evomoe_ctx* ctx, const evomoe_shape* shape, const float* dG_pairs,
+                                          const int32_t* tok_off, const int32_t* tok_rows, const float* gprime,
+                                          const uint64_t* mask_bits, float tau, const void* x, const float* Wg,
+                                          const float* dgprime_coef, float loss_scale, float* dWg, float* dbg,
+                                          void* dx, void* workspace, size_t workspace_bytes) {
+    CHECK_CTX_SHAPE();
+    REQUIRE_PTR(dG_pairs); REQUIRE_PTR(tok_off); REQUIRE_PTR(tok_rows); REQUIRE_PTR(gprime);
+    REQUIRE_PTR(mask_bits); REQUIRE_PTR(x); REQUIRE_PTR(Wg); REQUIRE_PTR(dWg); REQUIRE_PTR(dx);
+    OPTIONAL_PTR(dbg);
+    if (dgprime_coef && (reinterpret_cast<uintptr_t>(dgprime_coef) & 3u)) return EVOMOE_EINVAL;
+    if (!(tau > 0.f)) return EVOMOE_EINVAL;
+    if (!workspace || !aligned16(workspace) || workspace_bytes < gate_bwd_workspace_bytes(*shape))
+        return EVOMOE_EWORKSPACE;
+    return from_hip(launch_dts_gate_bwd(ctx->c, *shape, dG_pairs, tok_off, tok_rows, gprime, mask_bits,
+                                        tau, x, Wg, dWg, dbg, dx, workspace, dgprime_coef, loss_scale));
+}
+
+size_t evomoe_workspace_bytes_recompute(const evomoe_shape* shape) {
+    if (check_shape(shape) != EVOMOE_OK) return 0;
+    const size_t a = ffn_bwd_recompute_workspace_bytes(*shape), b = gate_bwd_workspace_bytes(*shape);
+    const size_t m = a > b ? a : b;
+    return (m + 255) & ~(size_t)255;
+}
+
+evomoe_status evomoe_expert_ffn_bwd_recompute(evomoe_ctx* ctx, const evomoe_shape* shape, const void* dO,
+                                              const void* x, const int32_t* pair_token,
+                                              const int32_t* expert_offsets, const void* W1, const float* b1,
+                                              const void* W2, void* dW1, float* db1, void* dW2, float* db2,
+                                              void* dXp, int accumulate, void* workspace,
+                                              size_t workspace_bytes) {
+    CHECK_CTX_SHAPE();
+    if (evomoe_status fs = check_ffn_shape(shape); fs != EVOMOE_OK) return fs;
+    REQUIRE_PTR(dO); REQUIRE_PTR(x); REQUIRE_PTR(expert_offsets); REQUIRE_PTR(W1); REQUIRE_PTR(W2);
+    REQUIRE_PTR(dXp);
+    OPTIONAL_PTR(pair_token); OPTIONAL_PTR(b1); OPTIONAL_PTR(dW1); OPTIONAL_PTR(db1); OPTIONAL_PTR(dW2);
+    OPTIONAL_PTR(db2);
+    if (!workspace || !aligned16(workspace) || workspace_bytes < ffn_bwd_recompute_workspace_bytes(*shape))
+        return EVOMOE_EWORKSPACE;
+    return from_hip(launch_expert_ffn_bwd_recompute(ctx->c, *shape, dO, x, pair_token, expert_offsets, W1, b1,
+                                                    W2, dW1, db1, dW2, db2, dXp, accumulate, workspace));
+}
+
+evomoe_status evomoe_schedule(int64_t iteration, int64_t T_S, int64_t T_D, float tau_hi, float tau_lo,
+                              evomoe_phase* phase_out) {
+    if (!phase_out || iteration < 0 || T_S < 0 || T_D < 0 || !(tau_hi > 0.f) || !(tau_lo > 0.f))
+        return EVOMOE_EINVAL;
+    if (iteration < T_S) {
+        phase_out->stage = 1; phase_out->top1 = 0; phase_out->tau = NAN;
+        return EVOMOE_OK;
+    }
+    const int64_t j = iteration - T_S;
+    phase_out->stage = 2;
+    if (j < T_D) {
+        phase_out->top1 = 0;
+        phase_out->tau = T_D == 1 ? tau_hi
+                                  : (float)((double)tau_hi - ((double)tau_hi - (double)tau_lo) * ((double)j / (double)(T_D - 1)));
+    } else {
+        phase_out->top1 = 1;
+        phase_out->tau = tau_lo;
+    }
+    return EVOMOE_OK;
 }
 
 evomoe_status evomoe_num_pairs(evomoe_ctx* ctx, const int64_t* num_pairs, int64_t* num_pairs_host) {

@@ -29,4 +29,24 @@ hipError_t launch_expert_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void
                                  db2, dXp, accumulate, workspace);
 }
 
+// Recompute variant: workspace = [H : P_cap x F][A : P_cap x F][the plain backward's workspace].
+static size_t act_bytes(const evomoe_shape& s) { return dh_bytes(s); }
+size_t ffn_bwd_recompute_workspace_bytes(const evomoe_shape& s) {
+    return 2 * act_bytes(s) + ffn_bwd_workspace_bytes(s);
+}
+hipError_t launch_expert_ffn_bwd_recompute(const Ctx& c, const evomoe_shape& s, const void* dO, const void* x,
+                                           const int32_t* pair_token, const int32_t* expert_offsets,
+                                           const void* W1, const float* b1, const void* W2, void* dW1,
+                                           float* db1, void* dW2, float* db2, void* dXp, int accumulate,
+                                           void* workspace) {
+    char* w = static_cast<char*>(workspace);
+    void* H = w;
+    void* A = w + act_bytes(s);
+    void* rest = w + 2 * act_bytes(s);
+    hipError_t err = launch_expert_ffn(c, s, x, pair_token, expert_offsets, W1, b1, W2, nullptr, H, A, nullptr);
+    if (err != hipSuccess) return err;
+    return launch_expert_ffn_bwd(c, s, dO, H, A, x, pair_token, expert_offsets, W1, W2, dW1, db1, dW2, db2,
+                                 dXp, accumulate, rest);
+}
+
 }  // namespace evomoe

@@ -638,7 +638,7 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
         a.B = (const bf16_t*)W1; a.ldb = s.d; a.b_group_stride = (int64_t)s.F * s.d;
         a.N = s.F; a.K = s.d; a.bias = b1; a.out1 = (bf16_t*)H; a.out2 = (bf16_t*)A;
         err = launch_gemm<L_NT, E_HA, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.F));
-        if (err != hipSuccess) return err;
+        if (err != hipSuccess || !O) return err;      // O == nullptr: recomputation of H and A only
     }
     {   // O = A W2^T + b2
         using Cfg = EVOMOE_CFG_GEMM2;

@@ -286,6 +286,7 @@ hipError_t simple_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, co
     hipLaunchKernelGGL((ffn_rows_kernel<TX, EPI_HA>), dim3(gx, (s.F + BN - 1) / BN), dim3(256), 0, c.stream,
                        (const TX*)x, s.d, pair_token, expert_offsets, s.E, s.P_cap, (const TX*)W1,
                        (int64_t)s.F * s.d, 1, s.d, s.F, s.d, b1, (const TX*)nullptr, (TX*)H, (TX*)A, s.act); }
+    if (!O) return hipGetLastError();     // O == nullptr: recomputation of H and A only
     // O = A W2^T + b2:  B_g(k, n) = W2[g][n][k]
     ProfScope ps(c, EVOMOE_K_FFN_GEMM2);
     hipLaunchKernelGGL((ffn_rows_kernel<TX, EPI_BIAS>), dim3(gx, (s.d + BN - 1) / BN), dim3(256), 0, c.stream,

@@ -363,13 +363,18 @@ hipError_t launch_dts_gate(const Ctx& c, const evomoe_shape& s, const void* x, c
 // backward
 // ---------------------------------------------------------------------------------------------
 // dz_sj = (g'_sj / tau) * (dG_sj - sum_i dG_si g'_si), with dG_si read from the token's rows
-// (tok_rows lists them in ascending expert id = ascending set bit of the mask).
+// (tok_rows lists them in ascending expert id = ascending set bit of the mask).  coef (optional, [E]):
+// a gradient with respect to g'_si that is the same for every token (the balance loss's), added to dG_si
+// for every expert, selected or not, times coef_scale.
 __global__ __launch_bounds__(256) void gate_dz_kernel(
     const float* __restrict__ dG_pairs, const int32_t* __restrict__ tok_off,
     const int32_t* __restrict__ tok_rows, const float* __restrict__ gprime,
     const uint64_t* __restrict__ mask_bits, float tau, int T, int E, int64_t P_cap,
-    float* __restrict__ dz)
+    const float* __restrict__ coef, float coef_scale, float* __restrict__ dz)
 {
+    __shared__ float scoef[64];
+    if (threadIdx.x < 64) scoef[threadIdx.x] = (coef && (int)threadIdx.x < E) ? coef_scale * coef[threadIdx.x] : 0.f;
+    __syncthreads();
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
     const uint64_t bits = mask_bits[t];
@@ -389,12 +394,17 @@ __global__ __launch_bounds__(256) void gate_dz_kernel(
             }
         }
     }
+    if (coef) {
+        float ic = 0.f;
+        for (int e = 0; e < E; ++e) ic += scoef[e] * gp[e];
+        inner += ic;
+    }
     int j = 0;
     for (int e = 0; e < E; ++e) {
-        float dg = 0.f;
+        float dg = scoef[e];
         if ((bits >> e) & 1ull) {
             const int64_t slot = base + j++;
-            if (slot < P_cap) dg = dG_pairs[tok_rows[slot]];
+            if (slot < P_cap) dg += dG_pairs[tok_rows[slot]];
         }
         dz[(size_t)t * E + e] = gp[e] / tau * (dg - inner);
     }
@@ -511,7 +521,8 @@ static hipError_t gate_bwd_t(const Ctx& c, const evomoe_shape& s, const float* d
 hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float* dG_pairs,
                                const int32_t* tok_off, const int32_t* tok_rows, const float* gprime,
                                const uint64_t* mask_bits, float tau, const void* x, const float* Wg,
-                               float* dWg, float* dbg, void* dx, void* workspace) {
+                               float* dWg, float* dbg, void* dx, void* workspace,
+                               const float* dgprime_coef, float coef_scale) {
     const int tc = gate_bwd_chunk_tokens(s);
     const int nchunk = (s.T + tc - 1) / tc;
     float* dz = (float*)workspace;
@@ -520,7 +531,8 @@ hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float*
     {
         ProfScope ps(c, EVOMOE_K_GATE_BWD_DZ);
         hipLaunchKernelGGL(gate_dz_kernel, dim3((s.T + 255) / 256), dim3(256), 0, c.stream, dG_pairs,
-                           tok_off, tok_rows, gprime, mask_bits, tau, s.T, s.E, s.P_cap, dz);
+                           tok_off, tok_rows, gprime, mask_bits, tau, s.T, s.E, s.P_cap, dgprime_coef,
+                           coef_scale, dz);
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
@@ -538,6 +550,67 @@ hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float*
     if (dbg)
         hipLaunchKernelGGL(sum_chunks_kernel, dim3(1), dim3(256), 0, c.stream, dbg_part, nchunk,
                            (size_t)s.E, dbg);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Balance loss (Eq. balance_loss): L = alpha N sum_i (count_i / T^2) sum_s g'_si and dL/dg'_si.
+// Pass 1: per-block column sums of g' (thread = (token lane, expert), fixed-order LDS reduction over the
+// token lanes).  Pass 2 (one block): block partials summed in block order, then the E terms in expert order.
+// ---------------------------------------------------------------------------------------------
+constexpr int kBalanceTokensPerBlock = 128;
+int balance_blocks(const evomoe_shape& s) { return (s.T + kBalanceTokensPerBlock - 1) / kBalanceTokensPerBlock; }
+
+__global__ __launch_bounds__(256) void balance_colsum_kernel(const float* __restrict__ gprime, int T, int E,
+                                                             float* __restrict__ partial)
+{
+    __shared__ float red[256];
+    const int EP = E <= 4 ? 4 : E <= 8 ? 8 : E <= 16 ? 16 : E <= 32 ? 32 : 64;     // expert lanes (power of two)
+    const int TL = 256 / EP;                                                        // token lanes
+    const int e = threadIdx.x % EP, tl = threadIdx.x / EP;
+    const int t0 = blockIdx.x * kBalanceTokensPerBlock;
+    const int t1 = min(T, t0 + kBalanceTokensPerBlock);
+    float acc = 0.f;
+    if (e < E)
+        for (int t = t0 + tl; t < t1; t += TL) acc += gprime[(size_t)t * E + e];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (tl == 0 && e < E) {
+        float sum = 0.f;
+        for (int l = 0; l < TL; ++l) sum += red[l * EP + e];
+        partial[(size_t)blockIdx.x * E + e] = sum;
+    }
+}
+
+__global__ __launch_bounds__(64) void balance_final_kernel(const float* __restrict__ partial, int nblk, int T, int E,
+                                                           const int32_t* __restrict__ counts, float alpha,
+                                                           float* __restrict__ loss, float* __restrict__ coef)
+{
+    __shared__ float term[64];
+    const int e = threadIdx.x;
+    float colsum = 0.f, cf = 0.f;
+    if (e < E) {
+        for (int b = 0; b < nblk; ++b) colsum += partial[(size_t)b * E + e];
+        cf = alpha * (float)E * ((float)counts[e] / ((float)T * (float)T));
+        if (coef) coef[e] = cf;
+    }
+    term[e] = cf * colsum;
+    __syncthreads();
+    if (e == 0) {
+        float L = 0.f;
+        for (int i = 0; i < E; ++i) L += term[i];
+        loss[0] = L;
+    }
+}
+
+hipError_t launch_balance_loss(const Ctx& c, const evomoe_shape& s, const float* gprime, const int32_t* counts,
+                               float alpha, float* loss, float* dgprime_coef) {
+    const int nblk = balance_blocks(s);
+    float* partial = reinterpret_cast<float*>(c.block_counts);
+    ProfScope ps(c, EVOMOE_K_BALANCE_LOSS);
+    hipLaunchKernelGGL(balance_colsum_kernel, dim3(nblk), dim3(256), 0, c.stream, gprime, s.T, s.E, partial);
+    hipLaunchKernelGGL(balance_final_kernel, dim3(1), dim3(64), 0, c.stream, partial, nblk, s.T, s.E, counts, alpha,
+                       loss, dgprime_coef);
     return hipGetLastError();
 }
 

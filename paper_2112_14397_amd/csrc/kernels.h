@@ -13,8 +13,13 @@ int gate_blocks(const Ctx& c, const evomoe_shape& s);   // grid size of the gate
 hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float* dG_pairs,
                                const int32_t* tok_off, const int32_t* tok_rows, const float* gprime,
                                const uint64_t* mask_bits, float tau, const void* x, const float* Wg,
-                               float* dWg, float* dbg, void* dx, void* workspace);
+                               float* dWg, float* dbg, void* dx, void* workspace,
+                               const float* dgprime_coef = nullptr, float coef_scale = 0.f);
 size_t gate_bwd_workspace_bytes(const evomoe_shape& s);
+// balance loss: scratch holds balance_blocks(s) * E floats of per-block column sums of g'
+int balance_blocks(const evomoe_shape& s);
+hipError_t launch_balance_loss(const Ctx& c, const evomoe_shape& s, const float* gprime, const int32_t* counts,
+                               float alpha, float* loss, float* dgprime_coef);
 
 // dispatch.hip
 hipError_t launch_dispatch(const Ctx& c, const evomoe_shape& s, const uint64_t* mask_bits,
@@ -44,5 +49,11 @@ hipError_t launch_expert_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void
                                  void* dW1, float* db1, void* dW2, float* db2, void* dXp,
                                  int accumulate, void* workspace);
 size_t ffn_bwd_workspace_bytes(const evomoe_shape& s);
+size_t ffn_bwd_recompute_workspace_bytes(const evomoe_shape& s);
+hipError_t launch_expert_ffn_bwd_recompute(const Ctx& c, const evomoe_shape& s, const void* dO, const void* x,
+                                           const int32_t* pair_token, const int32_t* expert_offsets,
+                                           const void* W1, const float* b1, const void* W2, void* dW1,
+                                           float* db1, void* dW2, float* db2, void* dXp, int accumulate,
+                                           void* workspace);
 
 }  // namespace evomoe

@@ -41,7 +41,7 @@ def mask_from_bits(bits_i64: np.ndarray, E: int) -> np.ndarray:
 class GpuLayer:
     """Device copies of one LayerInputs + the buffers of the layer."""
 
-    def __init__(self, inp: synth.LayerInputs, P_cap=None, backward=True):
+    def __init__(self, inp: synth.LayerInputs, P_cap=None, backward=True, recompute=False):
         cfg = inp.cfg
         self.cfg = cfg
         dt = B.torch_dtype(cfg.dtype)
@@ -53,37 +53,47 @@ class GpuLayer:
         self.dy = to_dev(inp.dy, dt)
         self.params = B.LayerParams(Wg=to_dev(inp.Wg), bg=to_dev(inp.bg), W1=to_dev(inp.W1, dt),
                                     b1=to_dev(inp.b1), W2=to_dev(inp.W2, dt), b2=to_dev(inp.b2))
-        self.buf = B.LayerBuffers(self.shape, backward=backward)
+        self.buf = B.LayerBuffers(self.shape, backward=backward, recompute=recompute)
+        self.recompute = recompute
 
-    def forward(self, tau, c):
-        B.layer_forward(self.ctx, self.buf, self.params, self.x, self.noise, float(tau), float(c))
+    def forward(self, tau, c, top1=False):
+        B.layer_forward(self.ctx, self.buf, self.params, self.x, self.noise, float(tau), float(c), top1=top1)
         return B.evomoe_num_pairs(self.ctx, self.buf.num_pairs)
 
-    def backward(self, tau):
-        B.layer_backward(self.ctx, self.buf, self.params, self.x, self.dy, float(tau))
+    def backward(self, tau, balance_alpha=None):
+        B.layer_backward(self.ctx, self.buf, self.params, self.x, self.dy, float(tau),
+                         balance_alpha=balance_alpha, recompute=self.recompute)
         torch.cuda.synchronize()
 
 
-def compare_forward(gl: GpuLayer, inp: synth.LayerInputs, tau, c, report=None, check_ffn=True):
+def compare_forward(gl: GpuLayer, inp: synth.LayerInputs, tau, c, report=None, check_ffn=True, top1=False):
     """Forward parity of every stage.  Returns (oracle forward, P, number of band pairs, number of
-    band pairs the two sides decided differently)."""
+    band pairs the two sides decided differently).  top1: Algorithm 2's Top-1 branch instead of the
+    threshold branch (c is ignored); the decision band is then a token whose two largest g' are within BAND."""
     cfg = inp.cfg
     rt = RTOL[cfg.dtype]
-    P = gl.forward(tau, c)
+    P = gl.forward(tau, c, top1=top1)
     b = gl.buf
     T, E = cfg.T, cfg.E
 
-    ref_gate = orc.dts_gate(inp.x, inp.Wg, inp.bg, inp.noise, tau, c)
+    ref_gate = orc.top1_gate(inp.x, inp.Wg, inp.bg, inp.noise, tau) if top1 else \
+        orc.dts_gate(inp.x, inp.Wg, inp.bg, inp.noise, tau, c)
     gp = np_of(b.gprime)
     ok, worst = tol_ok(gp, ref_gate.gprime, 1e-5)
     assert ok, f"gprime worst err/bound {worst:.3g}"
     mask = mask_from_bits(np_of(b.mask_bits), E)
-    band = np.abs(ref_gate.gprime - np.float64(np.float32(c))) < BAND
+    if top1:
+        top2 = np.sort(ref_gate.gprime, axis=1)[:, -2:] if E > 1 else np.zeros((T, 2))
+        near_tie = (top2[:, 1] - top2[:, 0]) < BAND if E > 1 else np.zeros(T, bool)
+        band = np.repeat(near_tie[:, None], E, axis=1)
+        assert (mask.sum(axis=1) == 1).all() and P == T, "Top-1: exactly one expert per token"
+    else:
+        band = np.abs(ref_gate.gprime - np.float64(np.float32(c))) < BAND
     diff = mask != ref_gate.mask
     # a fallback token's arg-max may be near-tied; treat rows that fell back on either side as band rows
     assert not (diff & ~band).any(), f"{int((diff & ~band).sum())} mask mismatches outside the band"
     n_band, n_flip = int(band.sum()), int(diff.sum())
-    override = mask if n_flip else None
+    override = mask if (n_flip or top1) else None
     fwd = orc.moe_layer_forward(inp.x, inp.Wg, inp.bg, inp.noise, tau, c, inp.W1, inp.b1, inp.W2,
                                 inp.b2, cfg.act, mask_override=override) if check_ffn else None
     g = fwd.gate if check_ffn else orc.dts_gate(inp.x, inp.Wg, inp.bg, inp.noise, tau, c, override)
@@ -125,16 +135,27 @@ def compare_forward(gl: GpuLayer, inp: synth.LayerInputs, tau, c, report=None, c
     return fwd, P, n_band, n_flip
 
 
-def compare_backward(gl: GpuLayer, inp: synth.LayerInputs, fwd: orc.LayerFwd, tau, slack=None):
+def compare_backward(gl: GpuLayer, inp: synth.LayerInputs, fwd: orc.LayerFwd, tau, slack=None, balance_alpha=None):
     """`slack` maps an output's name to a factor on its tolerance (end-to-end comparison of outputs
     that sit behind several bf16-stored intermediates; see compare_backward_stages)."""
     cfg = inp.cfg
     rt = RTOL[cfg.dtype]
     slack = slack or {}
-    gl.backward(tau)
+    gl.backward(tau, balance_alpha=balance_alpha)
     b = gl.buf
     P = int(fwd.disp.expert_offsets[cfg.E])
     ref = orc.moe_layer_backward(fwd, inp.dy, inp.x, inp.Wg, tau, inp.W1, inp.W2, cfg.act)
+    if balance_alpha is not None:
+        # L = L_task + L_balance (Training Objective, second stage): the balance loss and its gradient
+        loss_ref = orc.balance_loss(fwd.gate, balance_alpha)
+        coef_ref = orc.balance_loss_grad(fwd.gate, balance_alpha)
+        assert abs(float(np_of(b.bal_loss)[0]) - loss_ref) <= 1e-5 * abs(loss_ref), "balance loss"
+        ok, worst = tol_ok(np_of(b.bal_coef)[None, :], coef_ref[None, :], 1e-5)
+        assert ok, f"balance-loss gradient coefficients: worst err/bound {worst:.3g}"
+        dp = fwd.disp
+        ref.dz, ref.dWg, ref.dbg, dx_g = orc.dts_gate_bwd(ref.dG_pairs, dp.pair_token, dp.pair_expert,
+                                                          fwd.gate.gprime, tau, inp.x, inp.Wg, dgprime_coef=coef_ref)
+        ref.dx = ref.dx_experts + dx_g
     checks = (("dO", np_of(b.dO)[:P], ref.dO), ("dG_pairs", np_of(b.dG_pairs)[:P], ref.dG_pairs),
               ("dXp", np_of(b.dXp)[:P], ref.ffn.dXp),
               ("dW1", np_of(b.dW1), ref.ffn.dW1), ("db1", np_of(b.db1), ref.ffn.db1),
@@ -201,25 +222,31 @@ def _relu_patch(cfg, fwd, H_gpu_rows, report, key):
 
 
 def compare_full_size_sampled(gl: GpuLayer, inp: synth.LayerInputs, tau, c, n_tokens=192, experts=None,
-                              seed=0, report=None):
+                              seed=0, report=None, top1=False):
     cfg = inp.cfg
     rt = RTOL[cfg.dtype]
     report = {} if report is None else report
     T, E = cfg.T, cfg.E
-    P = gl.forward(tau, c)
+    P = gl.forward(tau, c, top1=top1)
     gl.backward(tau)
     b = gl.buf
 
     # (a) gate and dispatch of every token
-    ref_gate = orc.dts_gate(inp.x, inp.Wg, inp.bg, inp.noise, tau, c)
+    ref_gate = orc.top1_gate(inp.x, inp.Wg, inp.bg, inp.noise, tau) if top1 else \
+        orc.dts_gate(inp.x, inp.Wg, inp.bg, inp.noise, tau, c)
     gp = np_of(b.gprime)
     ok, worst = tol_ok(gp, ref_gate.gprime, 1e-5)
     assert ok, f"gprime worst err/bound {worst:.3g}"
     mask = mask_from_bits(np_of(b.mask_bits), E)
-    band = np.abs(ref_gate.gprime - np.float64(np.float32(c))) < BAND
+    if top1:
+        top2 = np.sort(ref_gate.gprime, axis=1)[:, -2:]
+        band = np.repeat(((top2[:, 1] - top2[:, 0]) < BAND)[:, None], E, axis=1)
+        assert (mask.sum(axis=1) == 1).all() and P == T
+    else:
+        band = np.abs(ref_gate.gprime - np.float64(np.float32(c))) < BAND
     diff = mask != ref_gate.mask
     assert not (diff & ~band).any(), f"{int((diff & ~band).sum())} mask mismatches outside the band"
-    g = orc.dts_gate(inp.x, inp.Wg, inp.bg, inp.noise, tau, c, mask if diff.any() else None)
+    g = orc.dts_gate(inp.x, inp.Wg, inp.bg, inp.noise, tau, c, mask if (diff.any() or top1) else None)
     dp = orc.dispatch(g.mask, g.G)
     np.testing.assert_array_equal(np_of(b.counts), g.counts)
     np.testing.assert_array_equal(np_of(b.k), g.k)
