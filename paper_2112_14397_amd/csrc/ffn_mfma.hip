@@ -646,7 +646,11 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
         a.A = (const bf16_t*)A; a.lda = s.F; a.a_rows = nullptr;
         a.B = (const bf16_t*)W2; a.ldb = s.F; a.b_group_stride = (int64_t)s.d * s.F;
         a.N = s.d; a.K = s.F; a.bias = b2; a.out1 = (bf16_t*)O; a.out2 = nullptr;
-        err = launch_gemm<L_NT, E_BIAS, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.d));
+        // few rows (late in the sweep, Top-1): the big tiles would leave most compute units without a tile
+        if (row_tiles<Cfg>(s) * ctiles<Cfg>(s.d) < (int64_t)c.num_cu * 3 / 2)
+            err = launch_gemm<L_NT, E_BIAS, CfgDuo>(c, a, row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(s.d));
+        else
+            err = launch_gemm<L_NT, E_BIAS, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.d));
     }
     return err;
 }
@@ -673,7 +677,10 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
         a.A = (const bf16_t*)dH; a.lda = s.F; a.B = (const bf16_t*)W1; a.ldb = s.d;
         a.b_group_stride = (int64_t)s.F * s.d; a.N = s.d; a.K = s.F; a.Hin = nullptr;
         a.out1 = (bf16_t*)dXp;
-        err = launch_gemm<L_NN, E_NONE, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.d));
+        if (row_tiles<Cfg>(s) * ctiles<Cfg>(s.d) < (int64_t)c.num_cu * 3 / 2)
+            err = launch_gemm<L_NN, E_NONE, CfgDuo>(c, a, row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(s.d));
+        else
+            err = launch_gemm<L_NN, E_NONE, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.d));
         if (err != hipSuccess) return err;
     }
     a.accumulate = accumulate;

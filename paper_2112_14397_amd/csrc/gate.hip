@@ -410,63 +410,107 @@ __global__ __launch_bounds__(256) void gate_dz_kernel(
     }
 }
 
-// One block = TC tokens x 256 columns k of x.  Thread k keeps W_g[k,:] and a partial dWg[k,:] in
-// registers, walks the chunk's tokens:  dx[s,k] += <dz[s,:], W_g[k,:]>,  dWg_part[k,:] += x[s,k] dz[s,:].
-template <typename TX, int EP>
+// CPT consecutive elements of a row <-> floats, one vector access (CPT = 1, 2 or 4)
+template <typename TX, int CPT> struct RowVec;
+template <int CPT> struct RowVec<float, CPT> {
+    __device__ static __forceinline__ void load(const float* p, float* o) {
+        if (CPT == 4) { const f32x4 v = *reinterpret_cast<const f32x4*>(p); o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w; }
+        else if (CPT == 2) { const float2 v = *reinterpret_cast<const float2*>(p); o[0] = v.x; o[1] = v.y; }
+        else o[0] = *p;
+    }
+    __device__ static __forceinline__ void store(float* p, const float* o) {
+        if (CPT == 4) { const f32x4 v = {o[0], o[1], o[2], o[3]}; *reinterpret_cast<f32x4*>(p) = v; }
+        else if (CPT == 2) { *reinterpret_cast<float2*>(p) = make_float2(o[0], o[1]); }
+        else *p = o[0];
+    }
+};
+template <int CPT> struct RowVec<bf16_t, CPT> {
+    __device__ static __forceinline__ void load(const bf16_t* p, float* o) {
+        if (CPT == 4) { const u32x2 v = *reinterpret_cast<const u32x2*>(p); o[0] = lo_bf16(v.x); o[1] = hi_bf16(v.x); o[2] = lo_bf16(v.y); o[3] = hi_bf16(v.y); }
+        else if (CPT == 2) { const uint32_t v = *reinterpret_cast<const uint32_t*>(p); o[0] = lo_bf16(v); o[1] = hi_bf16(v); }
+        else o[0] = Elem<bf16_t>::load(p);
+    }
+    __device__ static __forceinline__ void store(bf16_t* p, const float* o) {
+        if (CPT == 4) { const u32x2 v = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])}; *reinterpret_cast<u32x2*>(p) = v; }
+        else if (CPT == 2) { *reinterpret_cast<uint32_t*>(p) = pack_bf16x2(o[0], o[1]); }
+        else Elem<bf16_t>::store(p, o[0]);
+    }
+};
+
+// One block = TC tokens x 256*CPT columns of x.  A thread owns CPT consecutive columns k: it keeps W_g[k,:]
+// and a partial dWg[k,:] in registers and walks the chunk's tokens:
+//   dx[s,k] += <dz[s,:], W_g[k,:]>,   dWg_part[k,:] += x[s,k] dz[s,:].
+template <typename TX, int EP, int CPT>
 __global__ __launch_bounds__(256) void gate_bwd_kernel(
     const float* __restrict__ dz, const TX* __restrict__ x, const float* __restrict__ Wg,
     int T, int d, int E, int TC, TX* __restrict__ dx, float* __restrict__ dWg_part,
     float* __restrict__ dbg_part)
 {
-    extern __shared__ float sdz[];          // [TC][E]
+    extern __shared__ float sdz[];          // [TC][EP], zero beyond E
     const int chunk = blockIdx.x;
     const int s0 = chunk * TC;
     const int ns = min(TC, T - s0);
-    for (int i = threadIdx.x; i < ns * E; i += 256) sdz[i] = dz[(size_t)s0 * E + i];
+    for (int i = threadIdx.x; i < ns * EP; i += 256) {
+        const int s = i / EP, e = i % EP;
+        sdz[i] = (e < E) ? dz[(size_t)(s0 + s) * E + e] : 0.f;
+    }
     __syncthreads();
-    const int k = blockIdx.y * 256 + threadIdx.x;
     if (blockIdx.y == 0 && threadIdx.x < E) {     // bias gradient partial: sum_s dz[s,e]
         float sb = 0.f;
-        for (int s = 0; s < ns; ++s) sb += sdz[s * E + threadIdx.x];
+        for (int s = 0; s < ns; ++s) sb += sdz[s * EP + threadIdx.x];
         dbg_part[(size_t)chunk * E + threadIdx.x] = sb;
     }
+    const int k = (blockIdx.y * 256 + threadIdx.x) * CPT;
     if (k >= d) return;
-    float w[EP], g[EP];
+    float w[CPT][EP], g[CPT][EP];
 #pragma unroll
-    for (int e = 0; e < EP; ++e) {
-        w[e] = (e < E) ? Wg[(size_t)k * E + e] : 0.f;
-        g[e] = 0.f;
-    }
-    // tokens in groups of 8: the group's loads of x and dx are issued together, then used
-    for (int sb = 0; sb < ns; sb += 8) {
-        float xv[8], dxv[8];
+    for (int c = 0; c < CPT; ++c)
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int e = 0; e < EP; ++e) {
+            w[c][e] = (e < E) ? Wg[(size_t)(k + c) * E + e] : 0.f;
+            g[c][e] = 0.f;
+        }
+    // tokens in groups of UG: the group's loads of x and dx are issued together, then used
+    constexpr int UG = CPT == 1 ? 8 : 4;
+    for (int sb = 0; sb < ns; sb += UG) {
+        float xv[UG][CPT], dxv[UG][CPT];
+#pragma unroll
+        for (int u = 0; u < UG; ++u) {
             const int s = min(sb + u, ns - 1);
             const size_t off = (size_t)(s0 + s) * d + k;
-            xv[u] = Elem<TX>::load(x + off);
-            dxv[u] = Elem<TX>::load(dx + off);
+            RowVec<TX, CPT>::load(x + off, xv[u]);
+            RowVec<TX, CPT>::load(dx + off, dxv[u]);
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < UG; ++u) {
             const int s = sb + u;
             if (s < ns) {
-                float acc = 0.f;
+                float acc[CPT];
 #pragma unroll
-                for (int e = 0; e < EP; ++e) {
-                    if (e < E) {
-                        const float z = sdz[s * E + e];
-                        acc += z * w[e];
-                        g[e] += xv[u] * z;
-                    }
+                for (int c = 0; c < CPT; ++c) acc[c] = 0.f;
+#pragma unroll
+                for (int e4 = 0; e4 < EP; e4 += 4) {
+                    const f32x4 z4 = *reinterpret_cast<const f32x4*>(&sdz[s * EP + e4]);
+                    const float z[4] = {z4.x, z4.y, z4.z, z4.w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int c = 0; c < CPT; ++c) {
+                            acc[c] += z[q] * w[c][e4 + q];
+                            g[c][e4 + q] += xv[u][c] * z[q];
+                        }
                 }
-                Elem<TX>::store(dx + (size_t)(s0 + s) * d + k, dxv[u] + acc);
+#pragma unroll
+                for (int c = 0; c < CPT; ++c) acc[c] += dxv[u][c];
+                RowVec<TX, CPT>::store(dx + (size_t)(s0 + s) * d + k, acc);
             }
         }
     }
 #pragma unroll
-    for (int e = 0; e < EP; ++e)
-        if (e < E) dWg_part[((size_t)chunk * d + k) * E + e] = g[e];
+    for (int c = 0; c < CPT; ++c)
+#pragma unroll
+        for (int e = 0; e < EP; ++e)
+            if (e < E) dWg_part[((size_t)chunk * d + k + c) * E + e] = g[c][e];
 }
 
 // out[i] = sum over chunks (ascending) of part[chunk][i]
@@ -487,10 +531,10 @@ __global__ __launch_bounds__(256) void sum_chunks_kernel(const float* __restrict
 }
 
 static int gate_bwd_chunk_tokens(const evomoe_shape& s) {
-    int tc = 64;
-    while ((s.T + tc - 1) / tc > 128) tc *= 2;
-    // LDS holds [TC][E] floats; stay within 64 KB
-    while ((size_t)tc * s.E * 4 > 60 * 1024 && tc > 16) tc /= 2;
+    int tc = 32;
+    while ((s.T + tc - 1) / tc > 256) tc *= 2;
+    // LDS holds [TC][E rounded up to 16] floats; stay within 64 KB
+    while ((size_t)tc * (((s.E + 15) / 16) * 16) * 4 > 60 * 1024 && tc > 16) tc /= 2;
     return tc;
 }
 
@@ -504,16 +548,17 @@ template <typename TX>
 static hipError_t gate_bwd_t(const Ctx& c, const evomoe_shape& s, const float* dz, const void* x,
                              const float* Wg, void* dx, float* dWg_part, float* dbg_part, int tc,
                              int nchunk) {
-    dim3 grid(nchunk, (s.d + 255) / 256);
-    const size_t lds = (size_t)tc * s.E * sizeof(float);
     const int ep = ((s.E + 15) / 16) * 16;
-#define EVOMOE_GB(EPV)                                                                           \
-    hipLaunchKernelGGL((gate_bwd_kernel<TX, EPV>), grid, dim3(256), lds, c.stream, dz,           \
+    const int cpt = ep == 16 ? 4 : ep == 32 ? 2 : 1;         // columns per thread (register budget: 2*CPT*EP)
+    dim3 grid(nchunk, (s.d + 256 * cpt - 1) / (256 * cpt));
+    const size_t lds = (size_t)tc * ep * sizeof(float);
+#define EVOMOE_GB(EPV, CPTV)                                                                     \
+    hipLaunchKernelGGL((gate_bwd_kernel<TX, EPV, CPTV>), grid, dim3(256), lds, c.stream, dz,     \
                        (const TX*)x, Wg, s.T, s.d, s.E, tc, (TX*)dx, dWg_part, dbg_part)
-    if (ep == 16) EVOMOE_GB(16);
-    else if (ep == 32) EVOMOE_GB(32);
-    else if (ep == 48) EVOMOE_GB(48);
-    else EVOMOE_GB(64);
+    if (ep == 16) EVOMOE_GB(16, 4);
+    else if (ep == 32) EVOMOE_GB(32, 2);
+    else if (ep == 48) EVOMOE_GB(48, 1);
+    else EVOMOE_GB(64, 1);
 #undef EVOMOE_GB
     return hipGetLastError();
 }
