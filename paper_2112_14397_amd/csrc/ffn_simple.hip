@@ -198,47 +198,58 @@ __global__ __launch_bounds__(256) void ffn_wgrad_kernel(
 // Pass 1: block = 64 columns (8 lanes x 16 bytes) x 32 row lanes, one of kColsumSplit row ranges of one
 // expert; f32 partial sums, tree-reduced over the row lanes in LDS, written to part[split][g][n].
 // Pass 2 adds the splits in order.  No atomics: the result is reproducible bit for bit.
-constexpr int kColsumSplit = 4;
+constexpr int kColsumSplit = 32;
 
+// A block streams whole row segments: CL column lanes x 16 bytes are contiguous in a row (up to 4 KB), RL = 256/CL
+// row lanes take alternate rows, four rows of loads in flight per thread.
 template <typename TX>
 __global__ __launch_bounds__(256) void ffn_colsum_part_kernel(
     const TX* __restrict__ Mx, int N, int E, const int32_t* __restrict__ expert_offsets, int64_t P_cap,
-    float* __restrict__ part)
+    int CL, float* __restrict__ part)
 {
     constexpr int KV = Elem<TX>::kVec;           // elements per 16-byte load
-    constexpr int CL = 64 / KV;                  // column lanes covering 64 columns
-    constexpr int RL = 256 / CL;                 // row lanes
-    __shared__ float red[RL][64 + 1];
+    extern __shared__ float red[];               // [RL][CL*KV]
+    const int RL = 256 / CL;
     const int g = blockIdx.y, split = blockIdx.z;
     const int cl = threadIdx.x % CL, rl = threadIdx.x / CL;
-    const int n = blockIdx.x * 64 + cl * KV;
+    const int n = (blockIdx.x * CL + cl) * KV;
     const int r0 = clamp_pairs(expert_offsets[g], P_cap), r1 = clamp_pairs(expert_offsets[g + 1], P_cap);
     const int per = (r1 - r0 + kColsumSplit - 1) / kColsumSplit;
     const int rb = r0 + split * per, re = min(r1, rb + per);
     float acc[KV];
 #pragma unroll
     for (int q = 0; q < KV; ++q) acc[q] = 0.f;
-    if (n < N) {
-        for (int r = rb + rl; r < re; r += RL) {
+    if (n < N && rl < RL) {
+        int r = rb + rl;
+        for (; r + 3 * RL < re; r += 4 * RL) {
+            float v[4][KV];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Elem<TX>::load_vec(Mx + (size_t)(r + u * RL) * N + n, v[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int q = 0; q < KV; ++q) acc[q] += v[u][q];
+        }
+        for (; r < re; r += RL) {
             float v[KV];
             Elem<TX>::load_vec(Mx + (size_t)r * N + n, v);
 #pragma unroll
             for (int q = 0; q < KV; ++q) acc[q] += v[q];
         }
     }
+    if (rl < RL) {
 #pragma unroll
-    for (int q = 0; q < KV; ++q) red[rl][cl * KV + q] = acc[q];
-    __syncthreads();
-    for (int half = RL / 2; half > 0; half >>= 1) {
-        if (rl < half) {
-#pragma unroll
-            for (int q = 0; q < KV; ++q) red[rl][cl * KV + q] += red[rl + half][cl * KV + q];
-        }
-        __syncthreads();
+        for (int q = 0; q < KV; ++q) red[(size_t)rl * CL * KV + cl * KV + q] = acc[q];
     }
-    if (threadIdx.x < 64) {
-        const int nn = blockIdx.x * 64 + threadIdx.x;
-        if (nn < N) part[((size_t)split * E + g) * N + nn] = red[0][threadIdx.x];
+    __syncthreads();
+    // row lanes added in order by the threads of lane 0
+    if (rl == 0 && n < N) {
+#pragma unroll
+        for (int q = 0; q < KV; ++q) {
+            float sum = 0.f;
+            for (int l = 0; l < RL; ++l) sum += red[(size_t)l * CL * KV + cl * KV + q];
+            part[((size_t)split * E + g) * N + n + q] = sum;
+        }
     }
 }
 
@@ -248,8 +259,13 @@ __global__ __launch_bounds__(256) void ffn_colsum_final_kernel(const float* __re
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
     float s = accumulate ? db[i] : 0.f;
+    for (int k0 = 0; k0 < kColsumSplit; k0 += 8) {        // eight loads in flight, added in split order
+        float v[8];
 #pragma unroll
-    for (int k = 0; k < kColsumSplit; ++k) s += part[(size_t)k * n + i];
+        for (int u = 0; u < 8; ++u) v[u] = part[(size_t)(k0 + u) * n + i];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
     db[i] = s;
 }
 
@@ -260,8 +276,14 @@ size_t colsum_scratch_bytes(const evomoe_shape& s) {
 template <typename TX>
 hipError_t launch_colsum(const Ctx& c, const evomoe_shape& s, const void* Mx, int N,
                          const int32_t* expert_offsets, float* db, int accumulate, float* scratch) {
-    hipLaunchKernelGGL(ffn_colsum_part_kernel<TX>, dim3((N + 63) / 64, s.E, kColsumSplit), dim3(256), 0,
-                       c.stream, (const TX*)Mx, N, s.E, expert_offsets, s.P_cap, scratch);
+    constexpr int KV = Elem<TX>::kVec;
+    const int vecs = (N + KV - 1) / KV;                       // 16-byte vectors per row
+    int CL = vecs >= 256 ? 256 : vecs;                        // column lanes (contiguous in a row)
+    if (CL > 128) CL = 256;                                   // 129..255 vectors: two column blocks of 256 lanes
+    const int RL = 256 / CL;
+    hipLaunchKernelGGL(ffn_colsum_part_kernel<TX>, dim3((vecs + CL - 1) / CL, s.E, kColsumSplit), dim3(256),
+                       (size_t)RL * CL * KV * sizeof(float), c.stream, (const TX*)Mx, N, s.E, expert_offsets,
+                       s.P_cap, CL, scratch);
     const size_t n = (size_t)s.E * N;
     hipLaunchKernelGGL(ffn_colsum_final_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, scratch, n,
                        db, accumulate);
