@@ -207,3 +207,40 @@ def test_argument_errors():
         B.evomoe_expert_ffn_bwd(gl.ctx, gl.shape, b.dO, b.H, b.A, gl.x, b.pair_token, b.expert_offsets,
                                 gl.params.W1, gl.params.W2, b.dW1, b.db1, b.dW2, b.db2, b.dXp, False, small)
     assert ei.value.status == B.EVOMOE_EWORKSPACE
+
+
+def test_step_can_be_captured_in_a_hip_graph_and_replayed():
+    """The steady-state calls allocate nothing, clear nothing with memsets and never synchronise, so a caller may
+    capture forward + backward in a HIP graph.  Replays (with eager work and synchronisations between them, at a
+    different temperature) must reproduce the eager result bit for bit."""
+    cfg = synth.LayerConfig("graph", T=600, d=128, E=8, F=256, act="gelu", dtype="bf16", taus=(1.0,),
+                            threshold=0.08, seed=91, bias_std=0.05)
+    inp = synth.make_layer_inputs(cfg)
+    H = _harness()
+    from paper_2112_14397_amd import binding as B
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        gl = H.GpuLayer(inp)                      # context bound to the side stream
+        b = gl.buf
+
+        def step(tau):
+            B.layer_forward(gl.ctx, b, gl.params, gl.x, gl.noise, tau, cfg.threshold)
+            B.layer_backward(gl.ctx, b, gl.params, gl.x, gl.dy, tau)
+
+        step(0.9); step(0.5)                      # first calls size the context's scratch
+        side.synchronize()
+        P = B.evomoe_num_pairs(gl.ctx, b.num_pairs)
+        want = {k: getattr(b, k).clone() for k in ("y", "dx", "dW1", "dW2", "dWg", "db1", "mask_bits", "tok_off")}
+        want_rows = b.tok_rows[:P].clone()        # entries beyond P are whatever an earlier, denser step left
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step(0.5)
+        for _ in range(3):
+            step(1.7)                             # eager work at another temperature in between
+            side.synchronize()
+            assert not torch.equal(b.mask_bits, want["mask_bits"])
+            g.replay()
+            side.synchronize()
+            for k, v in want.items():
+                assert torch.equal(getattr(b, k), v), f"{k} differs after a graph replay"
+            assert torch.equal(b.tok_rows[:P], want_rows)
