@@ -32,9 +32,9 @@ PEAK_HBM_GBS = 8000.0
 # profiles/ keeps (FETCH_SIZE, WRITE_SIZE; each scaled by what the counter reads for the --copy-probe copy):
 # average over the sweep's temperatures.  None where no such run has been summarised.
 MEASURED_TRAFFIC = {
-    # profiles/layer_gpt_pmc_fetch_size.txt: 438307.5 KiB x 1.9999; profiles/layer_gpt_pmc_write_size.txt:
-    # 157440.0 KiB x 1.0000 (algorithmic: 38969 pairs x (2d + 2F) x 2 B read + 2 x E*d*F x 2 B written = 7.50e8)
-    "gpt": int((438307.5 * 1.9999 + 157440.0 * 1.0) * 1024),
+    # profiles/layer_gpt_pmc_fetch_size.txt: 437092.1 KiB x 1.9999; profiles/layer_gpt_pmc_write_size.txt:
+    # 157494.4 KiB x 1.0000 (algorithmic: 38969 pairs x (2d + 2F) x 2 B read + 2 x E*d*F x 2 B written = 7.50e8)
+    "gpt": int((437092.1 * 1.9999 + 157494.4 * 1.0) * 1024),
 }
 
 
@@ -219,11 +219,29 @@ def main():
         allp = B.evomoe_profile_read(ctx)
         B.evomoe_profile_select(ctx, None)
         Psum = sum(P_of[t] for t in taus) * 3
+        Pavg = Psum / (3 * len(taus))
+        T, d, E, F = cfg.T, cfg.d, cfg.E, cfg.F
+        sz = 2 if cfg.dtype == "bf16" else 4
+        # algorithmic HBM bytes per launch of the streaming kernels (sweep-average pair count)
+        stream_bytes = {
+            "gate": T * (d * sz + E * 8 + 12),
+            "dispatch_hist": T * 8, "dispatch_scatter": T * 12 + Pavg * 16,
+            "combine": Pavg * d * sz + T * d * sz + Pavg * 8,
+            "combine_bwd": 2 * Pavg * d * sz + T * d * sz + Pavg * 12,
+            "ffn_bwd_dw1": 2 * Pavg * d * sz + Pavg * 4,
+            "ffn_bwd_db": Pavg * (F + d) * sz,
+            "dispatch_bwd": Pavg * d * sz + T * d * sz,
+            "gate_bwd_dz": T * E * 8 + Pavg * 8 + T * 12,
+            "gate_bwd_main": T * d * sz * 3 + T * E * 4,
+        }
         ks = {}
         for name, (ms, n) in allp.items():
             ent = {"avg_us": ms * 1e3 / n, "launches": n}
             if name in _gemm_kernels():
                 ent["tflops"] = _gemm_kernels()[name] * Psum * flops_per_pair_gemm / (ms * 1e-3) / 1e12
+            if name in stream_bytes:
+                ent["hbm_gbs"] = stream_bytes[name] / (ms * 1e-3 / n) / 1e9
+                ent["hbm_frac"] = ent["hbm_gbs"] / PEAK_HBM_GBS
             ks[name] = ent
         out["kernels"] = ks
 
