@@ -20,13 +20,24 @@ __global__ __launch_bounds__(256) void combine_kernel(
         float acc[KV];
 #pragma unroll
         for (int q = 0; q < KV; ++q) acc[q] = 0.f;
-        for (int64_t j = j0; j < j1; ++j) {
-            const int r = tok_rows[j];
-            const float g = pair_gate[r];
-            float val[KV];
-            Elem<TX>::load_vec(O + (size_t)r * d + v * KV, val);
+        // four rows at a time: indices, then weights and vectors, are loaded together; added in ascending
+        // expert order
+        for (int64_t j = j0; j < j1; j += 4) {
+            int r[4];
 #pragma unroll
-            for (int q = 0; q < KV; ++q) acc[q] += g * val[q];
+            for (int u = 0; u < 4; ++u) r[u] = tok_rows[j + u < j1 ? j + u : j1 - 1];
+            float g[4], val[4][KV];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                g[u] = pair_gate[r[u]];
+                Elem<TX>::load_vec(O + (size_t)r[u] * d + v * KV, val[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (j + u < j1) {
+#pragma unroll
+                    for (int q = 0; q < KV; ++q) acc[q] += g[u] * val[u][q];
+                }
         }
         Elem<TX>::store_vec(y + (size_t)t * d + v * KV, acc);
     }

@@ -214,12 +214,21 @@ __global__ __launch_bounds__(256) void dispatch_bwd_kernel(
         float acc[KV];
 #pragma unroll
         for (int q = 0; q < KV; ++q) acc[q] = 0.f;
-        for (int64_t j = j0; j < j1; ++j) {
-            const int r = tok_rows[j];
-            float val[KV];
-            Elem<TX>::load_vec(dXp + (size_t)r * d + v * KV, val);
+        // four rows at a time: their indices, then their vectors, are loaded together (the loads of one row
+        // depend on each other, those of different rows do not); added in ascending expert order
+        for (int64_t j = j0; j < j1; j += 4) {
+            int r[4];
 #pragma unroll
-            for (int q = 0; q < KV; ++q) acc[q] += val[q];
+            for (int u = 0; u < 4; ++u) r[u] = tok_rows[j + u < j1 ? j + u : j1 - 1];
+            float val[4][KV];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Elem<TX>::load_vec(dXp + (size_t)r[u] * d + v * KV, val[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (j + u < j1) {
+#pragma unroll
+                    for (int q = 0; q < KV; ++q) acc[q] += val[u][q];
+                }
         }
         Elem<TX>::store_vec(dx + (size_t)t * d + v * KV, acc);
     }

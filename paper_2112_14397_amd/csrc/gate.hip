@@ -513,21 +513,29 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(
             if (e < E) dWg_part[((size_t)chunk * d + k + c) * E + e] = g[c][e];
 }
 
-// out[i] = sum over chunks (ascending) of part[chunk][i]
+// out[i] = sum over chunks of part[chunk][i]: four thread groups take a quarter of the chunks each (ascending,
+// 16 independent loads in flight), then the four partial sums are added in group order.  Fixed order: reproducible.
 __global__ __launch_bounds__(256) void sum_chunks_kernel(const float* __restrict__ part, int nchunk,
                                                          size_t n, float* __restrict__ out)
 {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
+    __shared__ float red[4][64];
+    const int o = threadIdx.x & 63, gq = threadIdx.x >> 6;
+    const size_t i = (size_t)blockIdx.x * 64 + o;
+    const int per = (nchunk + 3) / 4;
+    const int c_lo = gq * per, c_hi = min(nchunk, c_lo + per);
     float s = 0.f;
-    for (int c0 = 0; c0 < nchunk; c0 += 16) {      // 16 independent loads in flight, added in chunk order
-        float v[16];
+    if (i < n) {
+        for (int c0 = c_lo; c0 < c_hi; c0 += 16) {
+            float v[16];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) v[u] = (c0 + u < nchunk) ? part[(size_t)(c0 + u) * n + i] : 0.f;
+            for (int u = 0; u < 16; ++u) v[u] = (c0 + u < c_hi) ? part[(size_t)(c0 + u) * n + i] : 0.f;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) s += v[u];
+            for (int u = 0; u < 16; ++u) s += v[u];
+        }
     }
-    out[i] = s;
+    red[gq][o] = s;
+    __syncthreads();
+    if (gq == 0 && i < n) out[i] = ((red[0][o] + red[1][o]) + red[2][o]) + red[3][o];
 }
 
 static int gate_bwd_chunk_tokens(const evomoe_shape& s) {
@@ -590,7 +598,7 @@ hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float*
     if (err != hipSuccess) return err;
     const size_t n = (size_t)s.d * s.E;
     ProfScope ps(c, EVOMOE_K_GATE_BWD_REDUCE);
-    hipLaunchKernelGGL(sum_chunks_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, dWg_part,
+    hipLaunchKernelGGL(sum_chunks_kernel, dim3((n + 63) / 64), dim3(256), 0, c.stream, dWg_part,
                        nchunk, n, dWg);
     if (dbg)
         hipLaunchKernelGGL(sum_chunks_kernel, dim3(1), dim3(256), 0, c.stream, dbg_part, nchunk,
