@@ -362,52 +362,36 @@ hipError_t launch_dts_gate(const Ctx& c, const evomoe_shape& s, const void* x, c
 // ---------------------------------------------------------------------------------------------
 // backward
 // ---------------------------------------------------------------------------------------------
-// dz_sj = (g'_sj / tau) * (dG_sj - sum_i dG_si g'_si), with dG_si read from the token's rows
-// (tok_rows lists them in ascending expert id = ascending set bit of the mask).  coef (optional, [E]):
-// a gradient with respect to g'_si that is the same for every token (the balance loss's), added to dG_si
-// for every expert, selected or not, times coef_scale.
+// dz_sj = (g'_sj / tau) * (dG_sj - sum_i dG_si g'_si).  EP lanes (a power of two >= E) work on one token, lane e
+// on expert e: dG_se sits in row tok_rows[tok_off[s] + (number of selected experts below e)] (rows of a token
+// are listed in ascending expert id); the inner product is a butterfly sum over the EP lanes (fixed order).
+// coef (optional, [E]): a gradient with respect to g'_si that is the same for every token (the balance
+// loss's), added to dG_si for every expert, selected or not, times coef_scale.
+template <int EP>
 __global__ __launch_bounds__(256) void gate_dz_kernel(
     const float* __restrict__ dG_pairs, const int32_t* __restrict__ tok_off,
     const int32_t* __restrict__ tok_rows, const float* __restrict__ gprime,
     const uint64_t* __restrict__ mask_bits, float tau, int T, int E, int64_t P_cap,
     const float* __restrict__ coef, float coef_scale, float* __restrict__ dz)
 {
-    __shared__ float scoef[64];
-    if (threadIdx.x < 64) scoef[threadIdx.x] = (coef && (int)threadIdx.x < E) ? coef_scale * coef[threadIdx.x] : 0.f;
-    __syncthreads();
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= T) return;
-    const uint64_t bits = mask_bits[t];
-    const int64_t base = tok_off[t];
-    const float* gp = gprime + (size_t)t * E;
-    float inner = 0.f;
-    {
-        uint64_t b = bits;
-        int j = 0;
-        while (b) {
-            const int e = __ffsll((unsigned long long)b) - 1;
-            b &= b - 1;
-            const int64_t slot = base + j++;
-            if (slot < P_cap) {
-                const int r = tok_rows[slot];
-                inner += dG_pairs[r] * gp[e];
-            }
-        }
-    }
-    if (coef) {
-        float ic = 0.f;
-        for (int e = 0; e < E; ++e) ic += scoef[e] * gp[e];
-        inner += ic;
-    }
-    int j = 0;
-    for (int e = 0; e < E; ++e) {
-        float dg = scoef[e];
+    constexpr int TPB = 256 / EP;
+    const int e = threadIdx.x % EP, tl = threadIdx.x / EP;
+    const int t = blockIdx.x * TPB + tl;
+    const bool ok = t < T && e < E;
+    float g = 0.f, dg = 0.f;
+    if (ok) {
+        const uint64_t bits = mask_bits[t];
+        g = gprime[(size_t)t * E + e];
+        if (coef) dg = coef_scale * coef[e];
         if ((bits >> e) & 1ull) {
-            const int64_t slot = base + j++;
+            const int64_t slot = (int64_t)tok_off[t] + __popcll(bits & ((1ull << e) - 1ull));
             if (slot < P_cap) dg += dG_pairs[tok_rows[slot]];
         }
-        dz[(size_t)t * E + e] = gp[e] / tau * (dg - inner);
     }
+    float inner = dg * g;
+#pragma unroll
+    for (int o = EP >> 1; o > 0; o >>= 1) inner += __shfl_xor(inner, o, 64);
+    if (ok) dz[(size_t)t * E + e] = g / tau * (dg - inner);
 }
 
 // CPT consecutive elements of a row <-> floats, one vector access (CPT = 1, 2 or 4)
@@ -470,17 +454,20 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(
             w[c][e] = (e < E) ? Wg[(size_t)(k + c) * E + e] : 0.f;
             g[c][e] = 0.f;
         }
-    // tokens in groups of UG: the group's loads of x and dx are issued together, then used
+    // tokens in groups of UG: a group's loads of x and dx are issued together, one group ahead of the group
+    // being multiplied (double buffer), so that their latency runs under the arithmetic
     constexpr int UG = CPT == 1 ? 8 : 4;
-    for (int sb = 0; sb < ns; sb += UG) {
-        float xv[UG][CPT], dxv[UG][CPT];
+    float xv[2][UG][CPT], dxv[2][UG][CPT];
+    auto load_group = [&](int sb, int buf) {
 #pragma unroll
         for (int u = 0; u < UG; ++u) {
             const int s = min(sb + u, ns - 1);
             const size_t off = (size_t)(s0 + s) * d + k;
-            RowVec<TX, CPT>::load(x + off, xv[u]);
-            RowVec<TX, CPT>::load(dx + off, dxv[u]);
+            RowVec<TX, CPT>::load(x + off, xv[buf][u]);
+            RowVec<TX, CPT>::load(dx + off, dxv[buf][u]);
         }
+    };
+    auto use_group = [&](int sb, int buf) {
 #pragma unroll
         for (int u = 0; u < UG; ++u) {
             const int s = sb + u;
@@ -497,14 +484,21 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(
 #pragma unroll
                         for (int c = 0; c < CPT; ++c) {
                             acc[c] += z[q] * w[c][e4 + q];
-                            g[c][e4 + q] += xv[u][c] * z[q];
+                            g[c][e4 + q] += xv[buf][u][c] * z[q];
                         }
                 }
 #pragma unroll
-                for (int c = 0; c < CPT; ++c) acc[c] += dxv[u][c];
+                for (int c = 0; c < CPT; ++c) acc[c] += dxv[buf][u][c];
                 RowVec<TX, CPT>::store(dx + (size_t)(s0 + s) * d + k, acc);
             }
         }
+    };
+    if (ns > 0) load_group(0, 0);
+    for (int sb = 0; sb < ns; sb += 2 * UG) {
+        if (sb + UG < ns) load_group(sb + UG, 1);
+        use_group(sb, 0);
+        if (sb + 2 * UG < ns) load_group(sb + 2 * UG, 0);
+        if (sb + UG < ns) use_group(sb + UG, 1);
     }
 #pragma unroll
     for (int c = 0; c < CPT; ++c)
@@ -583,9 +577,16 @@ hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float*
     float* dbg_part = dWg_part + (size_t)nchunk * s.d * s.E;
     {
         ProfScope ps(c, EVOMOE_K_GATE_BWD_DZ);
-        hipLaunchKernelGGL(gate_dz_kernel, dim3((s.T + 255) / 256), dim3(256), 0, c.stream, dG_pairs,
-                           tok_off, tok_rows, gprime, mask_bits, tau, s.T, s.E, s.P_cap, dgprime_coef,
-                           coef_scale, dz);
+#define EVOMOE_DZ(EPV)                                                                                   \
+    hipLaunchKernelGGL(gate_dz_kernel<EPV>, dim3((s.T + 256 / EPV - 1) / (256 / EPV)), dim3(256), 0, c.stream,  \
+                       dG_pairs, tok_off, tok_rows, gprime, mask_bits, tau, s.T, s.E, s.P_cap, dgprime_coef,     \
+                       coef_scale, dz)
+        if (s.E <= 4) EVOMOE_DZ(4);
+        else if (s.E <= 8) EVOMOE_DZ(8);
+        else if (s.E <= 16) EVOMOE_DZ(16);
+        else if (s.E <= 32) EVOMOE_DZ(32);
+        else EVOMOE_DZ(64);
+#undef EVOMOE_DZ
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
