@@ -102,3 +102,27 @@ def test_recompute_full_size_gpt_whole_layer():
     fwd, P, _, _ = H.compare_forward(gl, inp, tau, cfg.threshold)
     gl.buf.H.fill_(float("nan")); gl.buf.A.fill_(float("nan"))
     H.compare_backward(gl, inp, fwd, tau, slack=H.CHAIN_SLACK)
+
+
+def test_argument_errors_of_the_added_entry_points():
+    cfg, inp = small("bf16")
+    gl = H.GpuLayer(inp)
+    b, s = gl.buf, gl.shape
+    gl.forward(0.7, cfg.threshold)
+    with pytest.raises(B.EvoMoEError) as e:           # recompute needs its own, larger workspace
+        B.evomoe_expert_ffn_bwd_recompute(gl.ctx, s, b.dO, gl.x, b.pair_token, b.expert_offsets, gl.params.W1,
+                                          gl.params.b1, gl.params.W2, b.dW1, b.db1, b.dW2, b.db2, b.dXp, False,
+                                          b.workspace)
+    assert e.value.status == B.EVOMOE_EWORKSPACE
+    with pytest.raises(B.EvoMoEError) as e:
+        B.evomoe_balance_loss(gl.ctx, s, b.gprime, b.counts, 0.1, None, b.bal_coef)
+    assert e.value.status == B.EVOMOE_EINVAL
+    with pytest.raises(B.EvoMoEError) as e:
+        B.evomoe_dts_gate_top1(gl.ctx, s, gl.x, gl.params.Wg, None, None, 0.0, b.gprime, None, b.mask_bits, b.counts, None)
+    assert e.value.status == B.EVOMOE_EINVAL
+    # the bf16 matrix-core FFN refuses layers narrower than one 64-wide slab; the gate does not
+    narrow = B.make_shape(cfg.T, 32, cfg.E, 48, "bf16", "gelu", cfg.T * cfg.E)
+    with pytest.raises(B.EvoMoEError) as e:
+        B.evomoe_expert_ffn(gl.ctx, narrow, gl.x, b.pair_token, b.expert_offsets, gl.params.W1, None, gl.params.W2,
+                            None, b.H, b.A, b.O)
+    assert e.value.status == B.EVOMOE_EUNSUPPORTED
