@@ -104,7 +104,6 @@ evomoe_status evomoe_create(evomoe_ctx** ctx_out, void* hip_stream) {
     }
     c.num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     c.status_dev = small;          // [0] status flag
-    c.ticket_dev = small + 32;     // own 128-byte line
     if (hipMemsetAsync(small, 0, 256, c.stream) != hipSuccess ||
         ensure_scratch(c, 65536) != EVOMOE_OK) {
         (void)hipFree(small);

@@ -103,7 +103,6 @@ struct Ctx {
     int device;
     int num_cu;
     int32_t* status_dev;      // [1] device flag: bit0 = capacity overflow
-    int32_t* ticket_dev;      // [1] arrival counter of the gate's last-block reduction
     int32_t* block_counts;    // scratch for per-block expert histograms
     size_t block_counts_elems;
     uint16_t* wg_planes;      // bf16 gate: W_g split into three bf16 terms, transposed ([3][16*NE][d])

@@ -161,8 +161,21 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: lives in an SGPR
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, kg = lane >> 5;
+    __shared__ int tstart[65];      // NT/NN: number of row tiles before each expert (tstart[E] = all of them)
     if (tid <= q0.E) offs[tid] = clamp_pairs(q0.expert_offsets[tid], q0.P_cap);
     __syncthreads();
+    if (LAYOUT != L_TN) {
+        if (tid == 0) {
+            int acc_t = 0;
+            for (int e = 0; e < q0.E; ++e) {
+                tstart[e] = acc_t;
+                acc_t += (offs[e + 1] - offs[e] + BM - 1) / BM;
+            }
+            tstart[q0.E] = acc_t;
+        }
+        __syncthreads();
+    }
+    int cur_e = 0;                  // expert of the previous tile: row tiles only grow from tile to tile
 
     // LDS byte offsets of this lane's operand fragments inside one stage (k-step 0), per MFMA tile
     int fa_off[TM], fb_off[TN_];
@@ -223,21 +236,11 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
         } else {
             const int rt = tile / nct;
             n0 = (tile % nct) * BN;
-            int seen = 0;
-            bool found = false;
-            for (int e = 0; e < p.E; ++e) {
-                const int ne = offs[e + 1] - offs[e];
-                const int nt = (ne + BM - 1) / BM;
-                if (rt < seen + nt) {
-                    g = e;
-                    row0 = offs[e] + (rt - seen) * BM;
-                    rows = min(BM, offs[e + 1] - row0);
-                    found = true;
-                    break;
-                }
-                seen += nt;
-            }
-            if (!found) break;
+            if (rt >= tstart[p.E]) break;
+            while (rt >= tstart[cur_e + 1]) ++cur_e;      // resumes where the previous tile's search ended
+            g = cur_e;
+            row0 = offs[g] + (rt - tstart[g]) * BM;
+            rows = min(BM, offs[g + 1] - row0);
             kbeg = 0;
             kend = p.K;
         }

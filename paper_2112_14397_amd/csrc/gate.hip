@@ -4,7 +4,7 @@
 // bf16 MFMAs against a hi/mid/lo split of W_g for a bf16 layer: a selection decided by g' > c must not
 // move), + bias + Gumbel noise, temperature softmax,
 // strict threshold with the arg-max fallback, bit mask, per-token k, and the per-expert histogram
-// (per-block partial counts; the last block to finish adds them up in block order).
+// (per-block partial counts, added up by gate_counts_kernel).
 #include <type_traits>
 
 #include "kernels.h"
@@ -18,14 +18,13 @@ namespace evomoe {
 // element r of lane (q = lane/16, i16 = lane%16) is token row 4q+r, expert column 16n+i16).
 // Adds the four waves' tiles in wave order (fixed order => reproducible bits), then 16/RT threads per
 // token apply bias, noise, temperature softmax, the strict threshold and the arg-max fallback, write
-// g', weights, mask and k, and build the per-expert histogram (per-block partials, summed by the last
-// block to arrive).
+// g', weights, mask and k, and build the per-expert histogram (per-block partials, summed afterwards by
+// gate_counts_kernel).
 template <int NE, int RT>
 __device__ __forceinline__ void gate_finish(
     f32x4 (&acc)[RT][NE], const float* __restrict__ bg, const float* __restrict__ noise, float tau, float c,
     int T, int E, float* __restrict__ gprime, float* __restrict__ gate_w, uint64_t* __restrict__ mask_bits,
-    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts, int32_t* __restrict__ ticket,
-    int32_t* __restrict__ counts)
+    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts)
 {
     constexpr int TPB = 16 * RT;           // tokens per block
     constexpr int EP = 16 * NE;            // experts padded to MFMA tiles
@@ -168,8 +167,7 @@ __global__ __launch_bounds__(256) void dts_gate_kernel(
     const TX* __restrict__ x, const float* __restrict__ Wg, const float* __restrict__ bg,
     const float* __restrict__ noise, float tau, float c, int T, int d, int E,
     float* __restrict__ gprime, float* __restrict__ gate_w, uint64_t* __restrict__ mask_bits,
-    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts,
-    int32_t* __restrict__ ticket, int32_t* __restrict__ counts)
+    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts)
 {
     constexpr int KV = Elem<TX>::kVec;     // k's per 16-byte load
     constexpr int KB = 4 * KV;             // k's per slab (4 lane groups x KV)
@@ -210,8 +208,7 @@ __global__ __launch_bounds__(256) void dts_gate_kernel(
             }
         }
     }
-    gate_finish<NE, RT>(acc, bg, noise, tau, c, T, E, gprime, gate_w, mask_bits, k_per_token, block_counts,
-                        ticket, counts);
+    gate_finish<NE, RT>(acc, bg, noise, tau, c, T, E, gprime, gate_w, mask_bits, k_per_token, block_counts);
 }
 
 // bf16 layer.  x is exact in bf16, so W_g is split into three bf16 terms (hi + mid + lo carry all 24
@@ -242,8 +239,7 @@ __global__ __launch_bounds__(256) void dts_gate_bf16_kernel(
     const bf16_t* __restrict__ x, const bf16_t* __restrict__ planes, const float* __restrict__ bg,
     const float* __restrict__ noise, float tau, float c, int T, int d, int E,
     float* __restrict__ gprime, float* __restrict__ gate_w, uint64_t* __restrict__ mask_bits,
-    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts,
-    int32_t* __restrict__ ticket, int32_t* __restrict__ counts)
+    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts)
 {
     constexpr int TPB = 16 * RT, EP = 16 * NE;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -285,8 +281,7 @@ __global__ __launch_bounds__(256) void dts_gate_bf16_kernel(
             }
         }
     }
-    gate_finish<NE, RT>(acc, bg, noise, tau, c, T, E, gprime, gate_w, mask_bits, k_per_token, block_counts,
-                        ticket, counts);
+    gate_finish<NE, RT>(acc, bg, noise, tau, c, T, E, gprime, gate_w, mask_bits, k_per_token, block_counts);
 }
 
 static int pick_rt(const Ctx& c, int T) {
@@ -314,11 +309,11 @@ static hipError_t gate_launch_t(const Ctx& c, const evomoe_shape& s, const void*
                            s.E, ep, c.wg_planes);
         hipLaunchKernelGGL((dts_gate_bf16_kernel<NE, RT>), dim3(blocks), dim3(256), 0, c.stream,
                            (const bf16_t*)x, (const bf16_t*)c.wg_planes, bg, noise, tau, thr, s.T, s.d, s.E,
-                           gprime, gate_w, mask_bits, k_per_token, c.block_counts, c.ticket_dev, counts);
+                           gprime, gate_w, mask_bits, k_per_token, c.block_counts);
     } else {
         hipLaunchKernelGGL((dts_gate_kernel<TX, NE, RT>), dim3(blocks), dim3(256), 0, c.stream,
                            (const TX*)x, Wg, bg, noise, tau, thr, s.T, s.d, s.E, gprime, gate_w,
-                           mask_bits, k_per_token, c.block_counts, c.ticket_dev, counts);
+                           mask_bits, k_per_token, c.block_counts);
     }
     hipLaunchKernelGGL(gate_counts_kernel, dim3(1), dim3(256), 0, c.stream, c.block_counts, blocks, s.E, counts);
     return hipGetLastError();
