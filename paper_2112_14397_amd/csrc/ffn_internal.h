@@ -16,7 +16,9 @@ hipError_t simple_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, c
 template <typename TX>
 hipError_t launch_colsum(const Ctx& c, const evomoe_shape& s, const void* Mx, int N,
                          const int32_t* expert_offsets, float* db, int accumulate, float* scratch);
-size_t colsum_scratch_bytes(const evomoe_shape& s);   // a multiple of 256 is reserved for it
+// [partials of the streaming column sums][bf16 layer: per-tile column sums of dH]; a multiple of 256
+size_t colsum_scratch_bytes(const evomoe_shape& s);
+size_t dh_colpart_bytes(const evomoe_shape& s);       // the second part alone (0 for a float32 layer)
 // the backward workspace is [dH : P_cap x F elements, rounded up to 256 B][bias-gradient partial sums]
 inline size_t dh_bytes(const evomoe_shape& s) {
     const size_t esz = s.dtype == EVOMOE_BF16 ? 2 : 4;

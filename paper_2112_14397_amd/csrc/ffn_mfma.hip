@@ -40,6 +40,7 @@ struct GemmArgs {
     const bf16_t* Hin;                  // E_ACTGRAD: pre-activations [P,N]
     bf16_t* out1;                       // C (H for E_HA)
     bf16_t* out2;                       // E_HA: A = act(H)
+    float* colpart;                     // E_ACTGRAD: per-tile column sums of C, [row tile][2][N] (or null)
     int act, accumulate;
 };
 
@@ -157,10 +158,9 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int offs[65];
 
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int tid = threadIdx.x, lane_id = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: lives in an SGPR
     const int wm = wave >> 1, wn = wave & 1;
-    const int l32 = lane & 31, kg = lane >> 5;
     __shared__ int tstart[65];      // NT/NN: number of row tiles before each expert (tstart[E] = all of them)
     if (tid <= q0.E) offs[tid] = clamp_pairs(q0.expert_offsets[tid], q0.P_cap);
     __syncthreads();
@@ -176,40 +176,6 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
         __syncthreads();
     }
     int cur_e = 0;                  // expert of the previous tile: row tiles only grow from tile to tile
-
-    // LDS byte offsets of this lane's operand fragments inside one stage (k-step 0), per MFMA tile
-    int fa_off[TM], fb_off[TN_];
-    const int s16 = lane & 15;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        if (G::A_KC) {
-            fa_off[i] = (wm * WM + i * 32 + l32) * (BK * 2);     // row base; the swizzled chunk is added per k-step
-        } else {
-            const int lb = (wm * WM + i * 32 + ((lane >> 4) & 1) * 16) >> 4;       // logical 32 B block
-            fa_off[i] = (kg * 8 + (s16 >> 2)) * (BM * 2) + ((lb ^ (2 * (s16 >> 2))) << 5) + ((s16 & 3) << 3);
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < TN_; ++j) {
-        if (G::B_KC) {
-            fb_off[j] = (wn * WN + j * 32 + l32) * (BK * 2);
-        } else {
-            const int lb = (wn * WN + j * 32 + ((lane >> 4) & 1) * 16) >> 4;
-            fb_off[j] = (kg * 8 + (s16 >> 2)) * (BN * 2) + ((lb ^ (2 * (s16 >> 2))) << 5) + ((s16 & 3) << 3);
-        }
-    }
-    // swizzle key of this lane's fragment rows (tile rows start at multiples of 32)
-    const int sw = (BK == 64) ? ((l32 >> 1) & 7) : ((l32 >> 2) & 3);
-
-    // This lane's role in the 1 KB load instruction number (wave + 4*i) of a tile:
-    //   k-contiguous: row (wave+4i)*KC_RPI + lane/KC_CH, physical chunk lane%KC_CH -> logical chunk ^ key(row)
-    //   k-strided   : k-row (wave+4i)*RPI + lane/CPR, physical chunk lane%CPR -> logical chunk via block ^ (k & 3)
-    const int kc_row = lane / KC_CH;
-    // key(row) of row (wave + 4i)*KC_RPI + kc_row does not depend on i
-    const int kc_key = (BK == 64) ? ((4 * (wave & 1) + (kc_row >> 1)) & 7) : ((kc_row >> 2) & 3);
-    const int kc_chunk = (lane % KC_CH) ^ kc_key;                           // logical 16 B chunk (8 k's)
-    const int ksA_row = lane / A_CPR, ksB_row = lane / B_CPR;
-    auto ks_col = [&](int pc, int krow) { return ((((pc >> 1) ^ (2 * (krow & 3))) << 1) | (pc & 1)) * 8; };
 
     // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber the blocks so that
     // one XCD works on a run of consecutive tiles (which share A row panels and B column panels) and the
@@ -253,6 +219,45 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
         const int nslab = (kend - kbeg + BK - 1) / BK;
         const bool ragged = (kend - kbeg) % BK != 0;     // block-uniform: the last slab is partial
         const bf16_t* Bg = (LAYOUT == L_TN) ? p.B : p.B + (int64_t)g * p.b_group_stride;
+
+        // Everything below that depends on the lane is recomputed for every tile from an opaque copy of the lane
+        // number: the values then die with the main loop instead of occupying registers through the epilogue.
+        int lane_t = lane_id;
+        asm volatile("" : "+v"(lane_t));
+        const int lane = lane_t;
+        // LDS byte offsets of this lane's operand fragments inside one stage (k-step 0), per MFMA tile
+        int fa_off[TM], fb_off[TN_];
+        const int s16 = lane & 15, l32 = lane & 31, kg = lane >> 5;
+    #pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if (G::A_KC) {
+                fa_off[i] = (wm * WM + i * 32 + l32) * (BK * 2);     // row base; the swizzled chunk is added per k-step
+            } else {
+                const int lb = (wm * WM + i * 32 + ((lane >> 4) & 1) * 16) >> 4;       // logical 32 B block
+                fa_off[i] = (kg * 8 + (s16 >> 2)) * (BM * 2) + ((lb ^ (2 * (s16 >> 2))) << 5) + ((s16 & 3) << 3);
+            }
+        }
+    #pragma unroll
+        for (int j = 0; j < TN_; ++j) {
+            if (G::B_KC) {
+                fb_off[j] = (wn * WN + j * 32 + l32) * (BK * 2);
+            } else {
+                const int lb = (wn * WN + j * 32 + ((lane >> 4) & 1) * 16) >> 4;
+                fb_off[j] = (kg * 8 + (s16 >> 2)) * (BN * 2) + ((lb ^ (2 * (s16 >> 2))) << 5) + ((s16 & 3) << 3);
+            }
+        }
+        // swizzle key of this lane's fragment rows (tile rows start at multiples of 32)
+        const int sw = (BK == 64) ? ((l32 >> 1) & 7) : ((l32 >> 2) & 3);
+
+        // This lane's role in the 1 KB load instruction number (wave + 4*i) of a tile:
+        //   k-contiguous: row (wave+4i)*KC_RPI + lane/KC_CH, physical chunk lane%KC_CH -> logical chunk ^ key(row)
+        //   k-strided   : k-row (wave+4i)*RPI + lane/CPR, physical chunk lane%CPR -> logical chunk via block ^ (k & 3)
+        const int kc_row = lane / KC_CH;
+        // key(row) of row (wave + 4i)*KC_RPI + kc_row does not depend on i
+        const int kc_key = (BK == 64) ? ((4 * (wave & 1) + (kc_row >> 1)) & 7) : ((kc_row >> 2) & 3);
+        const int kc_chunk = (lane % KC_CH) ^ kc_key;                           // logical 16 B chunk (8 k's)
+        const int ksA_row = lane / A_CPR, ksB_row = lane / B_CPR;
+        auto ks_col = [&](int pc, int krow) { return ((((pc >> 1) ^ (2 * (krow & 3))) << 1) | (pc & 1)) * 8; };
 
         // ---------------- global addresses: one scalar base per operand + 32-bit per-lane byte offsets ----
         // Rows / columns outside the tile are clamped onto valid ones (their products are never stored);
@@ -482,6 +487,12 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
         block_sync_lds();         // every wave is done reading operands: LDS becomes the epilogue's staging area
 
         // ---------------- epilogue: stage f32 rows through LDS, finish row-major ----------------
+        {
+        // (a fresh opaque copy of the lane number again: the epilogue's lane constants are not carried through
+        //  the main loop either)
+        int lane_e = lane_id;
+        asm volatile("" : "+v"(lane_e));
+        const int lane = lane_e, l32 = lane_e & 31, kg = lane_e >> 5;
         // acc[i][j][r] is C(row = i*32 + 8*(r/4) + 4*kg + r%4, col = j*32 + l32) of the wave tile.
         constexpr int ER = G::EPI_ROWS;
         float* stg = reinterpret_cast<float*>(smem) + wave * (ER * G::EPI_LD);
@@ -503,6 +514,8 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
                 bias8[4] = b1.x; bias8[5] = b1.y; bias8[6] = b1.z; bias8[7] = b1.w;
             }
         }
+        // E_ACTGRAD: column sums of the tile's valid rows (the bias gradient's share of this tile), f32
+        float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int pass = 0; pass < WM / ER; ++pass) {
             u32x4 hraw[EPI == E_ACTGRAD ? NIT : 1];
@@ -567,6 +580,9 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
 #pragma unroll
                             for (int q = 0; q < 8; ++q) v[q] *= act_grad_fast(h[q], EVOMOE_GELU_ERF);
                         }
+                        const float rv = trow < rows ? 1.f : 0.f;     // rows beyond the tile repeat its last row
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) cs[q] = fmaf(v[q], rv, cs[q]);
                     }
                     if (ok) store_out(p.out1 + grow * p.N + col_c, v);
                     if (EPI == E_HA) {
@@ -584,7 +600,53 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             }
             __builtin_amdgcn_wave_barrier();
         }
+        if (EPI == E_ACTGRAD && LAYOUT != L_TN) {
+            // the RPI lane groups hold different rows of the same columns: add them up, lane group 0 writes
+            // this wave's sums (rows wm*WM .. +WM-1 of the tile) as one row of the partial table
+            if (p.colpart) {
+#pragma unroll
+                for (int o = CPW; o < 64; o <<= 1)
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) cs[q] += __shfl_xor(cs[q], o, 64);
+                if (lane < CPW && col < p.N) {
+                    const int rt = tstart[g] + (row0 - offs[g]) / BM;
+                    float* dst = p.colpart + ((int64_t)rt * 2 + wm) * p.N + col_c;
+                    *reinterpret_cast<f32x4*>(dst) = f32x4{cs[0], cs[1], cs[2], cs[3]};
+                    *reinterpret_cast<f32x4*>(dst + 4) = f32x4{cs[4], cs[5], cs[6], cs[7]};
+                }
+            }
+        }
+        }
     }
+}
+
+// db[g, n] (+)= sum over expert g's row tiles (two partial rows each) of the per-tile column sums written by
+// the dH GEMM, added in row order: reproducible bit for bit.
+__global__ __launch_bounds__(256) void colpart_final_kernel(
+    const float* __restrict__ part, const int32_t* __restrict__ expert_offsets, int E, int64_t P_cap, int N,
+    int BM, float* __restrict__ db, int accumulate)
+{
+    const int g = blockIdx.y;
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    int t0 = 0, nt = 0;                  // first row tile of expert g, number of its row tiles
+    for (int e = 0; e <= g; ++e) {
+        const int r = clamp_pairs(expert_offsets[e + 1], P_cap) - clamp_pairs(expert_offsets[e], P_cap);
+        nt = (r + BM - 1) / BM;
+        if (e < g) t0 += nt;
+    }
+    if (n >= N) return;
+    const float* src = part + (int64_t)t0 * 2 * N + n;
+    float sum = accumulate ? db[(int64_t)g * N + n] : 0.f;
+    int i = 0;
+    for (; i + 8 <= 2 * nt; i += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(i + u) * N];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sum += v[u];
+    }
+    for (; i < 2 * nt; ++i) sum += src[(int64_t)i * N];
+    db[(int64_t)g * N + n] = sum;
 }
 
 // Tile configurations.  BIG: one block per compute unit, 256 accumulator registers per lane.
@@ -628,6 +690,12 @@ template <class Cfg> int64_t mtiles(int m) { return (m + Cfg::BM - 1) / Cfg::BM;
 
 }  // namespace
 
+// per-tile column sums of dH: two rows of F floats per row tile of the dH GEMM
+size_t dh_colpart_bytes(const evomoe_shape& s) {
+    if (s.dtype != EVOMOE_BF16) return 0;
+    return ((size_t)row_tiles<EVOMOE_CFG_DH>(s) * 2 * s.F * sizeof(float) + 255) & ~(size_t)255;
+}
+
 hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, const int32_t* pair_token,
                         const int32_t* expert_offsets, const void* W1, const float* b1, const void* W2,
                         const float* b2, void* H, void* A, void* O) {
@@ -665,13 +733,18 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
     GemmArgs a{};
     a.expert_offsets = expert_offsets; a.E = s.E; a.P_cap = s.P_cap; a.act = s.act;
     hipError_t err;
-    {   // dH = (dO W2) * act'(H)
+    // workspace behind dH: [column-sum partials of the streaming kernel][per-tile column sums of dH][gathered x]
+    float* scratch = reinterpret_cast<float*>(static_cast<char*>(dH) + dh_bytes(s));
+    float* colpart = reinterpret_cast<float*>(static_cast<char*>(dH) + dh_bytes(s) + colsum_scratch_bytes(s) -
+                                              dh_colpart_bytes(s));
+    {   // dH = (dO W2) * act'(H); its epilogue also leaves the column sums of every tile (for db1)
         using Cfg = EVOMOE_CFG_DH;
         ProfScope ps(c, EVOMOE_K_FFN_BWD_DH);
         a.A = (const bf16_t*)dO; a.lda = s.d; a.B = (const bf16_t*)W2; a.ldb = s.F;
         a.b_group_stride = (int64_t)s.d * s.F; a.N = s.F; a.K = s.d; a.Hin = (const bf16_t*)H;
-        a.out1 = (bf16_t*)dH;
+        a.out1 = (bf16_t*)dH; a.colpart = db1 ? colpart : nullptr;
         err = launch_gemm<L_NN, E_ACTGRAD, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.F));
+        a.colpart = nullptr;
         if (err != hipSuccess) return err;
     }
     {   // dXp = dH W1
@@ -718,10 +791,13 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
     }
     if (err != hipSuccess) return err;
     ProfScope ps(c, EVOMOE_K_FFN_BWD_DB);
-    float* scratch = reinterpret_cast<float*>(static_cast<char*>(dH) + dh_bytes(s));
     if (db2) err = launch_colsum<bf16_t>(c, s, dO, s.d, expert_offsets, db2, accumulate, scratch);
     if (err != hipSuccess) return err;
-    if (db1) err = launch_colsum<bf16_t>(c, s, dH, s.F, expert_offsets, db1, accumulate, scratch);
+    if (db1) {
+        hipLaunchKernelGGL(colpart_final_kernel, dim3((s.F + 255) / 256, s.E), dim3(256), 0, c.stream, colpart,
+                           expert_offsets, s.E, s.P_cap, s.F, (int)EVOMOE_CFG_DH::BM, db1, accumulate);
+        err = hipGetLastError();
+    }
     return err;
 }
 

@@ -270,7 +270,8 @@ __global__ __launch_bounds__(256) void ffn_colsum_final_kernel(const float* __re
 }
 
 size_t colsum_scratch_bytes(const evomoe_shape& s) {
-    return ((size_t)kColsumSplit * s.E * (s.d > s.F ? s.d : s.F) * sizeof(float) + 255) & ~(size_t)255;
+    return (((size_t)kColsumSplit * s.E * (s.d > s.F ? s.d : s.F) * sizeof(float) + 255) & ~(size_t)255) +
+           dh_colpart_bytes(s);
 }
 
 template <typename TX>
