@@ -502,6 +502,226 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(
             if (e < E) dWg_part[((size_t)chunk * d + k + c) * E + e] = g[c][e];
 }
 
+// ---- bf16 layer: both contractions of the gate backward on the matrix cores ------------------------------
+//   dx[s,k]   += sum_e dz[s,e] W_g[k,e]      (M = tokens, N = columns of x, K = experts)
+//   dWg[k,e]   = sum_s x[s,k] dz[s,e]        (M = columns of x, N = experts, K = tokens)
+// with v_mfma_f32_32x32x16_bf16.  x is bf16 already; the float32 factors are split into bf16 terms so that the
+// products stay (nearly) exact: dz = hi + mid + lo (all 24 mantissa bits; x dz is then exact, accumulated in
+// float32), W_g = hi + lo, and dx takes the three leading products (relative error 2^-16, far below the bf16
+// rounding of the stored dx).  Block = 4 waves = one run of tokens x 256 columns (64 per wave), walked in
+// chunks of 32 tokens; the chunk's dz terms sit in LDS as [token][expert] and feed dx directly (expert-contiguous)
+// and dWg through the transposing LDS read, as does the wave's x tile [token][column].
+namespace {
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kGbTok = 32;       // tokens per chunk
+constexpr int kGbCols = 256;     // columns per block
+
+struct GbPlan { int slices, tokens_per_block, nblk; };
+GbPlan gate_bwd_mfma_plan(const evomoe_shape& s) {
+    GbPlan p;
+    p.slices = (s.d + kGbCols - 1) / kGbCols;
+    int n = 512 / p.slices;                          // about two blocks per compute unit
+    const int cap = s.T / s.E > 32 ? s.T / s.E : 32; // bounds the partial dWg tables by the size of x
+    if (n > cap) n = cap;
+    if (n > 256) n = 256;
+    if (n < 1) n = 1;
+    p.tokens_per_block = ((s.T + n - 1) / n + kGbTok - 1) / kGbTok * kGbTok;
+    p.nblk = (s.T + p.tokens_per_block - 1) / p.tokens_per_block;
+    return p;
+}
+
+__device__ __forceinline__ bf16x8 lds_read_tr(const unsigned char* q, int row_bytes) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(q));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(q + 4 * row_bytes));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// KE = k-steps of 16 experts (dx), NE = tiles of 32 experts (dWg)
+template <int KE, int NE>
+__global__ __launch_bounds__(256, 2) void gate_bwd_mfma_kernel(
+    const float* __restrict__ dz, const bf16_t* __restrict__ x, const float* __restrict__ Wg, int T, int d, int E,
+    int tokens_per_block, bf16_t* __restrict__ dx, float* __restrict__ dWg_part, float* __restrict__ dbg_part)
+{
+    constexpr int EPL = 32 * NE;                     // experts per LDS row (zero beyond E)
+    constexpr int DZN = kGbTok * EPL / 256;          // dz values per thread and chunk
+    constexpr int PROW = EPL * 2, XROW = 128;        // LDS row bytes: dz terms, x tile
+    constexpr int STG_LD = 64 + 4;
+    __shared__ __align__(16) unsigned char planes[3][kGbTok * PROW];
+    __shared__ __align__(16) unsigned char xt[4][kGbTok * XROW];
+    __shared__ __align__(16) float stg[4][kGbTok * STG_LD];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, kg = lane >> 5, s16 = lane & 15, half = (lane >> 4) & 1;
+    const int blk = blockIdx.x, slice = blockIdx.y;
+    const int c0 = slice * kGbCols + wave * 64;      // this wave's first column
+    const int s_begin = blk * tokens_per_block, s_end = min(T, s_begin + tokens_per_block);
+    const int nch = (s_end - s_begin + kGbTok - 1) / kGbTok;
+
+    // W_g fragments of the dx product (B operand: k = expert, n = column), hi and lo terms, kept in registers
+    bf16x8 whi[2][KE], wlo[2][KE];
+#pragma unroll
+    for (int jc = 0; jc < 2; ++jc) {
+        const int col = min(c0 + jc * 32 + l32, d - 1);
+#pragma unroll
+        for (int ks = 0; ks < KE; ++ks)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int e = ks * 16 + kg * 8 + q;
+                const float w = e < E ? Wg[(size_t)col * E + e] : 0.f;
+                const bf16_t h = (bf16_t)w;
+                whi[jc][ks][q] = h;
+                wlo[jc][ks][q] = (bf16_t)(w - (float)h);
+            }
+    }
+    f32x16 acc_w[2][NE];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < NE; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_w[i][j][r] = 0.f;
+    float sb = 0.f;                                  // bias gradient partial (slice 0, thread = expert)
+
+    // global <-> thread mapping of a 32-token x 64-column wave tile: 8 lanes x 16 bytes per row, 8 rows per pass
+    const int trow = lane >> 3, tcol = (lane & 7) * 8;
+    const int gcol = min(c0 + tcol, d - 8);
+    const bool col_ok = c0 + tcol < d;
+    u32x4 xr[4], dxr[4];
+    float dzr[DZN];
+    auto load_x_dz = [&](int s0) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int t = min(s0 + it * 8 + trow, T - 1);
+            xr[it] = *reinterpret_cast<const u32x4*>(x + (size_t)t * d + gcol);
+        }
+#pragma unroll
+        for (int u = 0; u < DZN; ++u) {
+            const int i = tid + 256 * u, t = s0 + i / EPL, e = i % EPL;
+            dzr[u] = (e < E && t < T) ? dz[(size_t)t * E + e] : 0.f;
+        }
+    };
+    auto load_dx = [&](int s0) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int t = min(s0 + it * 8 + trow, T - 1);
+            dxr[it] = *reinterpret_cast<const u32x4*>(dx + (size_t)t * d + gcol);
+        }
+    };
+    if (nch > 0) {
+        load_x_dz(s_begin);
+        load_dx(s_begin);
+    }
+    for (int ch = 0; ch < nch; ++ch) {
+        const int s0 = s_begin + ch * kGbTok;
+        __syncthreads();                             // the previous chunk's readers are done with the dz terms
+#pragma unroll
+        for (int u = 0; u < DZN; ++u) {
+            const int i = tid + 256 * u;
+            const float v = dzr[u];
+            const bf16_t h = (bf16_t)v;
+            const float r1 = v - (float)h;
+            const bf16_t m = (bf16_t)r1;
+            const bf16_t l = (bf16_t)(r1 - (float)m);
+            reinterpret_cast<bf16_t*>(planes[0])[i] = h;
+            reinterpret_cast<bf16_t*>(planes[1])[i] = m;
+            reinterpret_cast<bf16_t*>(planes[2])[i] = l;
+        }
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+            *reinterpret_cast<u32x4*>(xt[wave] + (it * 8 + trow) * XROW + (lane & 7) * 16) = xr[it];
+        if (ch + 1 < nch) load_x_dz(s0 + kGbTok);    // next chunk's loads run under this chunk's arithmetic
+        __syncthreads();
+
+        if (slice == 0 && tid < E) {
+            for (int t = 0; t < kGbTok; ++t) {
+                const int i = t * EPL + tid;
+                sb += ((float)reinterpret_cast<const bf16_t*>(planes[0])[i] +
+                       (float)reinterpret_cast<const bf16_t*>(planes[1])[i]) +
+                      (float)reinterpret_cast<const bf16_t*>(planes[2])[i];
+            }
+        }
+        // dWg partial: A = x^T (rows = columns of x, k = token), B = dz terms (k = token, n = expert)
+#pragma unroll
+        for (int ks = 0; ks < kGbTok / 16; ++ks) {
+            bf16x8 xa[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                xa[i] = lds_read_tr(xt[wave] + (ks * 16 + kg * 8 + (s16 >> 2)) * XROW + (i * 2 + half) * 32 + (s16 & 3) * 8,
+                                    XROW);
+#pragma unroll
+            for (int j = 0; j < NE; ++j)
+#pragma unroll
+                for (int pl = 2; pl >= 0; --pl) {
+                    const bf16x8 zb = lds_read_tr(
+                        planes[pl] + (ks * 16 + kg * 8 + (s16 >> 2)) * PROW + (j * 2 + half) * 32 + (s16 & 3) * 8, PROW);
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        acc_w[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], zb, acc_w[i][j], 0, 0, 0);
+                }
+        }
+        // gate part of dx: A = dz terms (rows = tokens, k = expert), B = W_g terms
+        f32x16 acc_x[2];
+#pragma unroll
+        for (int jc = 0; jc < 2; ++jc)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_x[jc][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KE; ++ks) {
+            const int off = l32 * PROW + (ks * 16 + kg * 8) * 2;
+            const bf16x8 zh = *reinterpret_cast<const bf16x8*>(planes[0] + off);
+            const bf16x8 zm = *reinterpret_cast<const bf16x8*>(planes[1] + off);
+#pragma unroll
+            for (int jc = 0; jc < 2; ++jc) {
+                acc_x[jc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zm, whi[jc][ks], acc_x[jc], 0, 0, 0);
+                acc_x[jc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh, wlo[jc][ks], acc_x[jc], 0, 0, 0);
+                acc_x[jc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh, whi[jc][ks], acc_x[jc], 0, 0, 0);
+            }
+        }
+        // acc_x[jc][r] is (token 8*(r/4) + 4*kg + r%4, column jc*32 + l32): through LDS to row-major 16-byte pieces
+#pragma unroll
+        for (int jc = 0; jc < 2; ++jc)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                stg[wave][(8 * (r >> 2) + 4 * kg + (r & 3)) * STG_LD + jc * 32 + l32] = acc_x[jc][r];
+        __builtin_amdgcn_s_waitcnt(0xc07f);          // lgkmcnt(0): this wave's LDS writes have landed
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int row = it * 8 + trow;
+            const f32x4 v0 = *reinterpret_cast<const f32x4*>(&stg[wave][row * STG_LD + tcol]);
+            const f32x4 v1 = *reinterpret_cast<const f32x4*>(&stg[wave][row * STG_LD + tcol + 4]);
+            const u32x4 o = dxr[it];
+            u32x4 w;
+            w.x = pack_bf16x2(v0.x + lo_bf16(o.x), v0.y + hi_bf16(o.x));
+            w.y = pack_bf16x2(v0.z + lo_bf16(o.y), v0.w + hi_bf16(o.y));
+            w.z = pack_bf16x2(v1.x + lo_bf16(o.z), v1.y + hi_bf16(o.z));
+            w.w = pack_bf16x2(v1.z + lo_bf16(o.w), v1.w + hi_bf16(o.w));
+            if (col_ok && s0 + row < s_end) *reinterpret_cast<u32x4*>(dx + (size_t)(s0 + row) * d + gcol) = w;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (ch + 1 < nch) load_dx(s0 + kGbTok);
+    }
+    // acc_w[i][j][r] is (column c0 + i*32 + 8*(r/4) + 4*kg + r%4, expert j*32 + l32)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < NE; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int col = c0 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3), e = j * 32 + l32;
+                if (col < d && e < E) dWg_part[((size_t)blk * d + col) * E + e] = acc_w[i][j][r];
+            }
+    if (slice == 0 && tid < E) dbg_part[(size_t)blk * E + tid] = sb;
+}
+
+bool gate_bwd_use_mfma(const evomoe_shape& s) { return s.dtype == EVOMOE_BF16 && s.d % 8 == 0 && s.d >= 8; }
+
+}  // namespace
+
 // out[i] = sum over chunks of part[chunk][i]: four thread groups take a quarter of the chunks each (ascending,
 // 16 independent loads in flight), then the four partial sums are added in group order.  Fixed order: reproducible.
 __global__ __launch_bounds__(256) void sum_chunks_kernel(const float* __restrict__ part, int nchunk,
@@ -537,7 +757,8 @@ static int gate_bwd_chunk_tokens(const evomoe_shape& s) {
 
 size_t gate_bwd_workspace_bytes(const evomoe_shape& s) {
     const int tc = gate_bwd_chunk_tokens(s);
-    const size_t nchunk = (s.T + tc - 1) / tc;
+    size_t nchunk = (s.T + tc - 1) / tc;
+    if (gate_bwd_use_mfma(s)) nchunk = gate_bwd_mfma_plan(s).nblk;
     return ((size_t)s.T * s.E + nchunk * ((size_t)s.d * s.E + s.E)) * sizeof(float);
 }
 
@@ -566,7 +787,9 @@ hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float*
                                float* dWg, float* dbg, void* dx, void* workspace,
                                const float* dgprime_coef, float coef_scale) {
     const int tc = gate_bwd_chunk_tokens(s);
-    const int nchunk = (s.T + tc - 1) / tc;
+    const bool mfma = gate_bwd_use_mfma(s);
+    const GbPlan plan = gate_bwd_mfma_plan(s);
+    const int nchunk = mfma ? plan.nblk : (s.T + tc - 1) / tc;
     float* dz = (float*)workspace;
     float* dWg_part = dz + (size_t)s.T * s.E;
     float* dbg_part = dWg_part + (size_t)nchunk * s.d * s.E;
@@ -587,9 +810,22 @@ hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float*
     if (err != hipSuccess) return err;
     {
         ProfScope ps(c, EVOMOE_K_GATE_BWD_MAIN);
-        err = (s.dtype == EVOMOE_BF16)
-                  ? gate_bwd_t<bf16_t>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk)
-                  : gate_bwd_t<float>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk);
+        if (mfma) {
+            const dim3 grid(plan.nblk, plan.slices);
+#define EVOMOE_GBM(KEV, NEV)                                                                             \
+    hipLaunchKernelGGL((gate_bwd_mfma_kernel<KEV, NEV>), grid, dim3(256), 0, c.stream, dz, (const bf16_t*)x, Wg, \
+                       s.T, s.d, s.E, plan.tokens_per_block, (bf16_t*)dx, dWg_part, dbg_part)
+            if (s.E <= 16) EVOMOE_GBM(1, 1);
+            else if (s.E <= 32) EVOMOE_GBM(2, 1);
+            else if (s.E <= 48) EVOMOE_GBM(3, 2);
+            else EVOMOE_GBM(4, 2);
+#undef EVOMOE_GBM
+            err = hipGetLastError();
+        } else {
+            err = (s.dtype == EVOMOE_BF16)
+                      ? gate_bwd_t<bf16_t>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk)
+                      : gate_bwd_t<float>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk);
+        }
     }
     if (err != hipSuccess) return err;
     const size_t n = (size_t)s.d * s.E;

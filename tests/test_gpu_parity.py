@@ -54,6 +54,7 @@ RAGGED = [
     ("bf16-e64",      2100, 256, 64, 512, "gelu", "bf16", 0.012, 105),
     ("f32-e64",       600, 64,  64, 128, "gelu", "f32", 0.012, 106),
     ("bf16-e1",       130, 64,  1,  128, "gelu", "bf16", 0.5, 107),
+    ("bf16-e24",      900, 192, 24, 256, "gelu", "bf16", 0.03, 108),
 ]
 
 
