@@ -229,7 +229,10 @@ def main():
             "combine": Pavg * d * sz + T * d * sz + Pavg * 8,
             "combine_bwd": 2 * Pavg * d * sz + T * d * sz + Pavg * 12,
             "ffn_bwd_dw1": 2 * Pavg * d * sz + Pavg * 4,
-            "ffn_bwd_db": Pavg * (F + d) * sz,
+            # bf16 layer: db1 comes from per-tile column sums the dH GEMM leaves behind (two rows of F floats per
+            # 128-row tile, written there, read here); only dO is streamed again
+            "ffn_bwd_db": (Pavg * d * sz + (Pavg / 128 + E) * 2 * F * 4) if cfg.dtype == "bf16"
+                          else Pavg * (F + d) * sz,
             "dispatch_bwd": Pavg * d * sz + T * d * sz,
             "gate_bwd_dz": T * E * 8 + Pavg * 8 + T * 12,
             "gate_bwd_main": T * d * sz * 3 + T * E * 4,

@@ -25,104 +25,56 @@ __global__ __launch_bounds__(256) void dispatch_hist_kernel(
         block_counts[(size_t)blockIdx.x * E + tid] = wc[0][tid] + wc[1][tid] + wc[2][tid] + wc[3][tid];
 }
 
-// Pass 2 (one block): turns the [nblk][E] histogram table into  base[b][e] = first row of expert e's
-// tokens that live in block b,  the expert offsets, the per-block start of the token CSR, P, and the
-// capacity flag.  (A last-block-done ticket inside pass 1 would serialise one device-scope atomic per
-// block on one address; a separate tiny launch is cheaper.)
-__global__ __launch_bounds__(256) void dispatch_scan_kernel(
-    int nblk, int T, int E, int64_t P_cap,
-    int32_t* __restrict__ block_counts,   // [nblk][E] in: counts, out: bases
-    int32_t* __restrict__ tok_base,       // [nblk]
-    int32_t* __restrict__ expert_offsets, int32_t* __restrict__ tok_off,
-    int64_t* __restrict__ num_pairs, int32_t* __restrict__ status)
-{
-    __shared__ int tot[65];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // the table is walked in chunks staged through LDS
-    constexpr int kChunkInts = 8192;
-    __shared__ int tab[kChunkInts];
-    const int rows_per_chunk = min(kChunkInts / E, 256);      // one thread per block row in the scan
-    // pass A: column totals -> expert offsets
-    int mysum = 0;                                   // thread e < E accumulates column e
-    for (int b0 = 0; b0 < nblk; b0 += rows_per_chunk) {
-        const int nr = min(rows_per_chunk, nblk - b0);
-        for (int i = tid; i < nr * E; i += 256)
-            tab[i] = block_counts[(size_t)b0 * E + i];
-        __syncthreads();
-        if (tid < E)
-            for (int r = 0; r < nr; ++r) mysum += tab[r * E + tid];
-        __syncthreads();
-    }
-    if (tid < E) tot[tid + 1] = mysum;
-    if (tid == 0) tot[0] = 0;
-    __syncthreads();
-    if (tid == 0) {
-        for (int e = 0; e < E; ++e) tot[e + 1] += tot[e];     // inclusive scan -> offsets
-        const int64_t P = tot[E];
-        *num_pairs = P;
-        tok_off[T] = (int32_t)P;
-        if (P > P_cap) atomicOr(status, 1);
-    }
-    __syncthreads();
-    if (tid <= E) expert_offsets[tid] = tot[tid];
-    // pass B: per-expert running base over blocks (thread e), and per-block CSR base (block scan)
-    int run = (tid < E) ? tot[tid] : 0;
-    int carry = 0;                                   // pairs owned by tokens of earlier chunks (uniform)
-    __shared__ int wsum[4];
-    for (int b0 = 0; b0 < nblk; b0 += rows_per_chunk) {
-        const int nr = min(rows_per_chunk, nblk - b0);
-        for (int i = tid; i < nr * E; i += 256)
-            tab[i] = block_counts[(size_t)b0 * E + i];
-        __syncthreads();
-        // pairs of block b0+tid, then an exclusive scan over the chunk's blocks
-        int mine = 0;
-        if (tid < nr)
-            for (int e = 0; e < E; ++e) mine += tab[tid * E + e];
-        int incl = mine;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int v = __shfl_up(incl, o, 64);
-            if (lane >= o) incl += v;
-        }
-        if (lane == 63) wsum[wave] = incl;
-        __syncthreads();
-        int before = carry;
-        for (int w = 0; w < wave; ++w) before += wsum[w];
-        if (tid < nr) tok_base[b0 + tid] = before + incl - mine;
-        carry += wsum[0] + wsum[1] + wsum[2] + wsum[3];
-        if (tid < E) {
-            for (int r = 0; r < nr; ++r) {
-                const int cur = tab[r * E + tid];
-                tab[r * E + tid] = run;
-                run += cur;
-            }
-        }
-        __syncthreads();
-        for (int i = tid; i < nr * E; i += 256) block_counts[(size_t)b0 * E + i] = tab[i];
-        __syncthreads();
-    }
-}
-
-// Pass 2: one thread per token.  Row of pair (t, e) = base[block][e] + (selected tokens of e before t
-// inside the block), from wave ballots.  Writes pair_token / pair_gate at the row and the token's CSR.
+// Pass 2: one thread per token.  Every block first derives, from the [nblk][E] histogram table, what it needs
+// of the scan: the expert offsets (column totals, scanned over the experts) and, per expert, the number of
+// selected tokens in the blocks before it -- integer sums, so the order of addition is free.  (The table is a
+// few KB; reading it in every block is cheaper than a third launch for a serial scan.)  Then
+// row of pair (t, e) = offset[e] + earlier blocks' tokens of e + selected tokens of e before t inside the
+// block (wave ballots).  Writes pair_token / pair_gate at the row and the token's CSR; block 0 also writes
+// the expert offsets, P and the capacity flag.
+template <int EP>
 __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
-    const uint64_t* __restrict__ mask_bits, const float* __restrict__ scores, int T, int E,
-    int64_t P_cap, const int32_t* __restrict__ block_base, const int32_t* __restrict__ tok_base,
+    const uint64_t* __restrict__ mask_bits, const float* __restrict__ scores, int T, int E, int nblk,
+    int64_t P_cap, const int32_t* __restrict__ block_counts, int32_t* __restrict__ expert_offsets,
     int32_t* __restrict__ pair_token, float* __restrict__ pair_gate, int32_t* __restrict__ tok_off,
-    int32_t* __restrict__ tok_rows)
+    int32_t* __restrict__ tok_rows, int64_t* __restrict__ num_pairs, int32_t* __restrict__ status)
 {
-    __shared__ int wc[4][64];
+    __shared__ uint64_t wbal[4][64]; // wave w's ballot of expert e
+    __shared__ int wc[4][64];        // its population count
+    __shared__ int wbase[4][64];     // first row of expert e's tokens that live in wave w of this block
     __shared__ int base[64];
+    __shared__ int pre[64], tot[64], offs[65];
     __shared__ int wk[4];
+    __shared__ int tok_base_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int t = blockIdx.x * kDispatchTokens + tid;
     const uint64_t bits = (t < T) ? mask_bits[t] : 0ull;
     const uint64_t lt = (1ull << lane) - 1ull;
-    if (tid < E) base[tid] = block_base[(size_t)blockIdx.x * E + tid];
-    for (int e = 0; e < E; ++e) {
-        const uint64_t bal = __ballot((bits >> e) & 1ull);
-        if (lane == 0) wc[wave][e] = __popcll(bal);
+
+    // ---- the block's share of the scan ----
+    if (tid < 64) { pre[tid] = 0; tot[tid] = 0; }
+    __syncthreads();
+    {
+        const int e = tid % EP, rl = tid / EP;
+        int p = 0, a = 0;
+        if (e < E)
+            for (int b = rl; b < nblk; b += 256 / EP) {
+                const int v = block_counts[(size_t)b * E + e];
+                a += v;
+                if (b < (int)blockIdx.x) p += v;
+            }
+        if (a) atomicAdd(&tot[e], a);
+        if (p) atomicAdd(&pre[e], p);
     }
+    // ballots of this wave's 64 tokens, expert by expert; lane e keeps expert e's
+    uint64_t mybal = 0;
+#pragma unroll
+    for (int e = 0; e < EP; ++e) {
+        const uint64_t bal = __ballot((bits >> e) & 1ull);
+        if (lane == e) mybal = bal;
+    }
+    wbal[wave][lane] = mybal;
+    wc[wave][lane] = __popcll(mybal);
     // exclusive scan of k over the block's tokens -> CSR offsets
     const int k = __popcll(bits);
     int incl = k;
@@ -133,22 +85,66 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
     }
     if (lane == 63) wk[wave] = incl;
     __syncthreads();
-    int64_t slot = tok_base[blockIdx.x] + (incl - k);
+    if (wave == 0) {
+        const int v = lane < E ? tot[lane] : 0, pv = lane < E ? pre[lane] : 0;
+        int eincl = v, psum = pv;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int u = __shfl_up(eincl, o, 64);
+            if (lane >= o) eincl += u;
+            psum += __shfl_xor(psum, o, 64);
+        }
+        offs[lane + 1] = eincl;                      // offs[e + 1] = sum of the totals of experts 0..e
+        if (lane == 0) { offs[0] = 0; tok_base_s = psum; }
+        base[lane] = eincl - v + pv;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0) {
+        if (tid <= E) expert_offsets[tid] = offs[tid];
+        if (tid == 0) {
+            const int64_t P = offs[E];
+            *num_pairs = P;
+            tok_off[T] = (int32_t)P;
+            if (P > P_cap) atomicOr(status, 1);
+        }
+    }
+    {   // thread (w, e): one table entry each
+        int b = base[lane];
+        for (int u = 0; u < wave; ++u) b += wc[u][lane];
+        wbase[wave][lane] = b;
+    }
+    int64_t slot = tok_base_s + (incl - k);
     for (int w = 0; w < wave; ++w) slot += wk[w];
     if (t < T) tok_off[t] = (int32_t)slot;
+    __syncthreads();
 
-    for (int e = 0; e < E; ++e) {
-        const uint64_t bal = __ballot((bits >> e) & 1ull);
-        if ((bits >> e) & 1ull) {
-            int r = base[e] + __popcll(bal & lt);
-            for (int w = 0; w < wave; ++w) r += wc[w][e];
-            if ((int64_t)r < P_cap) {
-                pair_token[r] = t;
-                pair_gate[r] = scores[(size_t)t * E + e];
-            }
-            if (slot < P_cap) tok_rows[slot] = (int64_t)r < P_cap ? r : (int32_t)(P_cap - 1);
-            ++slot;
+    // every token walks its own selected experts (k of them, not E), eight per round: the round's scores are
+    // fetched together, then its pairs are written
+    uint64_t rem = bits;
+    while (rem) {
+        constexpr int U = 8;
+        int ee[U];
+        bool on[U];
+        float score[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            on[u] = rem != 0;
+            ee[u] = on[u] ? __ffsll((unsigned long long)rem) - 1 : 0;
+            rem &= rem - 1;                           // 0 stays 0
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u) score[u] = on[u] ? scores[(size_t)t * E + ee[u]] : 0.f;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (on[u]) {
+                const int r = wbase[wave][ee[u]] + __popcll(wbal[wave][ee[u]] & lt);
+                if ((int64_t)r < P_cap) {
+                    pair_token[r] = t;
+                    pair_gate[r] = score[u];
+                }
+                if (slot < P_cap) tok_rows[slot] = (int64_t)r < P_cap ? r : (int32_t)(P_cap - 1);
+                ++slot;
+            }
     }
 }
 
@@ -180,18 +176,21 @@ hipError_t launch_dispatch(const Ctx& c, const evomoe_shape& s, const uint64_t* 
                            float* pair_gate, int32_t* tok_off, int32_t* tok_rows, int64_t* num_pairs,
                            const void* x, void* x_perm) {
     const int nblk = dispatch_blocks(s);
-    int32_t* base = c.block_counts;
-    int32_t* tok_base = c.block_counts + (size_t)nblk * s.E;
+    int32_t* table = c.block_counts;
     {
         ProfScope ps(c, EVOMOE_K_DISPATCH_HIST);
-        hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, s.T, s.E, base);
-        hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(256), 0, c.stream, nblk, s.T, s.E, s.P_cap, base,
-                           tok_base, expert_offsets, tok_off, num_pairs, c.status_dev);
+        hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, s.T, s.E, table);
     }
     {
         ProfScope ps(c, EVOMOE_K_DISPATCH_SCATTER);
-        hipLaunchKernelGGL(dispatch_scatter_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, scores,
-                           s.T, s.E, s.P_cap, base, tok_base, pair_token, pair_gate, tok_off, tok_rows);
+#define EVOMOE_SCATTER(EPV)                                                                              \
+    hipLaunchKernelGGL(dispatch_scatter_kernel<EPV>, dim3(nblk), dim3(256), 0, c.stream, mask_bits, scores, s.T, \
+                       s.E, nblk, s.P_cap, table, expert_offsets, pair_token, pair_gate, tok_off, tok_rows,       \
+                       num_pairs, c.status_dev)
+        if (s.E <= 16) EVOMOE_SCATTER(16);
+        else if (s.E <= 32) EVOMOE_SCATTER(32);
+        else EVOMOE_SCATTER(64);
+#undef EVOMOE_SCATTER
     }
     if (x_perm) return launch_gather_rows(c, s, x, pair_token, expert_offsets, x_perm);
     return hipGetLastError();

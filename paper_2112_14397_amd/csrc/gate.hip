@@ -132,9 +132,9 @@ __device__ __forceinline__ void gate_finish(
     if (tid < E) block_counts[(size_t)blockIdx.x * E + tid] = cnt[tid];
 }
 
-// counts[e] = sum over gate blocks of block_counts[b][e]   (one block; integer, order-independent)
-__global__ __launch_bounds__(256) void gate_counts_kernel(const int32_t* __restrict__ block_counts,
-                                                          int nblk, int E, int32_t* __restrict__ counts)
+// counts[e] = sum over gate blocks of block_counts[b][e]   (one block of 1024 threads; integer, order-independent)
+__global__ __launch_bounds__(1024) void gate_counts_kernel(const int32_t* __restrict__ block_counts,
+                                                           int nblk, int E, int32_t* __restrict__ counts)
 {
     __shared__ int cnt[64];
     const int tid = threadIdx.x;
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void gate_counts_kernel(const int32_t* __restr
     __syncthreads();
     // thread -> (column e = tid % EW, row lane tid / EW): private sums first, one LDS atomic per thread
     const int EW = E <= 16 ? 16 : (E <= 32 ? 32 : 64);
-    const int e = tid % EW, rl = tid / EW, nrl = 256 / EW;
+    const int e = tid % EW, rl = tid / EW, nrl = 1024 / EW;
     int sum = 0;
     if (e < E)
         for (int b0 = rl; b0 < nblk; b0 += nrl * 8) {
@@ -254,40 +254,55 @@ __global__ __launch_bounds__(256) void dts_gate_bf16_kernel(
         for (int n = 0; n < NE; ++n) acc[rt][n] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const bf16x8 zero8 = {};
-    // k-blocks of 32, dealt round-robin to the four waves; lane group q holds k = 32*kb + 8q .. +7
-    for (int kb = wave; kb * 32 < d; kb += 4) {
+    // k-blocks of 32, dealt round-robin to the four waves; lane group q holds k = 32*kb + 8q .. +7.
+    // XU k-blocks per round: their x fragments are fetched together (one trip to memory per round), and the
+    // W_g terms of the next k-block are fetched while the current one multiplies.
+    constexpr int XU = RT * NE >= 8 ? 2 : (RT * NE >= 4 ? 4 : 8);
+    auto load_planes = [&](int kb, bf16x8 (&b)[NE][3]) {
         const int k0 = kb * 32 + q * 8;
         const bool kok = k0 < d;
-        bf16x8 a[RT];
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            const int t = t0 + rt * 16 + i16;
-            a[rt] = (kok && t < T) ? *reinterpret_cast<const bf16x8*>(x + (size_t)t * d + k0) : zero8;
-        }
 #pragma unroll
         for (int n = 0; n < NE; ++n) {
-            const bf16_t* wp = planes + (size_t)(n * 16 + i16) * d + k0;
-            bf16x8 b0 = zero8, b1 = zero8, b2 = zero8;
-            if (kok) {
-                b0 = *reinterpret_cast<const bf16x8*>(wp);
-                b1 = *reinterpret_cast<const bf16x8*>(wp + plane);
-                b2 = *reinterpret_cast<const bf16x8*>(wp + 2 * plane);
-            }
+            const bf16_t* wp = planes + (size_t)(n * 16 + i16) * d + (kok ? k0 : 0);
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+                b[n][pl] = kok ? *reinterpret_cast<const bf16x8*>(wp + pl * plane) : zero8;
+        }
+    };
+    for (int kb0 = wave; kb0 * 32 < d; kb0 += 4 * XU) {
+        bf16x8 a[XU][RT];
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const int k0 = (kb0 + 4 * u) * 32 + q * 8;
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
-                acc[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b2, acc[rt][n], 0, 0, 0);
-                acc[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b1, acc[rt][n], 0, 0, 0);
-                acc[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b0, acc[rt][n], 0, 0, 0);
+                const int t = t0 + rt * 16 + i16;
+                a[u][rt] = (k0 < d && t < T) ? *reinterpret_cast<const bf16x8*>(x + (size_t)t * d + k0) : zero8;
             }
+        }
+        bf16x8 b[2][NE][3];
+        load_planes(kb0, b[0]);
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            if (u + 1 < XU) load_planes(kb0 + 4 * (u + 1), b[(u + 1) & 1]);
+#pragma unroll
+            for (int n = 0; n < NE; ++n)
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    acc[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][rt], b[u & 1][n][2], acc[rt][n], 0, 0, 0);
+                    acc[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][rt], b[u & 1][n][1], acc[rt][n], 0, 0, 0);
+                    acc[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][rt], b[u & 1][n][0], acc[rt][n], 0, 0, 0);
+                }
         }
     }
     gate_finish<NE, RT>(acc, bg, noise, tau, c, T, E, gprime, gate_w, mask_bits, k_per_token, block_counts);
 }
 
 static int pick_rt(const Ctx& c, int T) {
-    // as many tokens per block as still leaves >= 2 blocks per compute unit
+    // as many tokens per block as still leaves a block for every compute unit (the W_g terms are read once per
+    // block, and fewer blocks leave fewer partial histograms to add up)
     for (int rt = 4; rt > 1; rt >>= 1)
-        if ((T + 16 * rt - 1) / (16 * rt) >= 2 * c.num_cu) return rt;
+        if ((T + 16 * rt - 1) / (16 * rt) >= c.num_cu) return rt;
     return 1;
 }
 
@@ -315,7 +330,7 @@ static hipError_t gate_launch_t(const Ctx& c, const evomoe_shape& s, const void*
                            (const TX*)x, Wg, bg, noise, tau, thr, s.T, s.d, s.E, gprime, gate_w,
                            mask_bits, k_per_token, c.block_counts);
     }
-    hipLaunchKernelGGL(gate_counts_kernel, dim3(1), dim3(256), 0, c.stream, c.block_counts, blocks, s.E, counts);
+    hipLaunchKernelGGL(gate_counts_kernel, dim3(1), dim3(1024), 0, c.stream, c.block_counts, blocks, s.E, counts);
     return hipGetLastError();
 }
 
