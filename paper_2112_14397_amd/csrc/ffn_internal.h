@@ -16,6 +16,12 @@ hipError_t simple_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, c
 template <typename TX>
 hipError_t launch_colsum(const Ctx& c, const evomoe_shape& s, const void* Mx, int N,
                          const int32_t* expert_offsets, float* db, int accumulate, float* scratch);
+// the streaming column sums split every expert's rows into this many ranges: part[split][g][n], added in order
+constexpr int kColsumSplit = 32;
+// first pass only: leaves part[kColsumSplit][E][N] in scratch
+template <typename TX>
+hipError_t launch_colsum_part(const Ctx& c, const evomoe_shape& s, const void* Mx, int N,
+                              const int32_t* expert_offsets, float* scratch);
 // [partials of the streaming column sums][bf16 layer: per-tile column sums of dH]; a multiple of 256
 size_t colsum_scratch_bytes(const evomoe_shape& s);
 size_t dh_colpart_bytes(const evomoe_shape& s);       // the second part alone (0 for a float32 layer)

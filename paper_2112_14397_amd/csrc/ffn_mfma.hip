@@ -620,33 +620,50 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
     }
 }
 
-// db[g, n] (+)= sum over expert g's row tiles (two partial rows each) of the per-tile column sums written by
-// the dH GEMM, added in row order: reproducible bit for bit.
-__global__ __launch_bounds__(256) void colpart_final_kernel(
-    const float* __restrict__ part, const int32_t* __restrict__ expert_offsets, int E, int64_t P_cap, int N,
-    int BM, float* __restrict__ db, int accumulate)
+// Both bias gradients in one launch.  The first E * gx1 blocks (expert g = b / gx1, 256 columns each):
+// db1[g, n] (+)= sum over expert g's row tiles (two partial rows each) of the per-tile column sums written by the
+// dH GEMM, in row order.  The remaining blocks: db2[i] (+)= sum over the splits of the streaming column sums of
+// dO, in split order.  Reproducible bit for bit.
+__global__ __launch_bounds__(256) void bias_grad_final_kernel(
+    const float* __restrict__ part1, const int32_t* __restrict__ expert_offsets, int E, int64_t P_cap, int N1,
+    int BM, int gx1, float* __restrict__ db1, const float* __restrict__ part2, size_t n2, float* __restrict__ db2,
+    int accumulate)
 {
-    const int g = blockIdx.y;
-    const int n = blockIdx.x * 256 + threadIdx.x;
-    int t0 = 0, nt = 0;                  // first row tile of expert g, number of its row tiles
-    for (int e = 0; e <= g; ++e) {
-        const int r = clamp_pairs(expert_offsets[e + 1], P_cap) - clamp_pairs(expert_offsets[e], P_cap);
-        nt = (r + BM - 1) / BM;
-        if (e < g) t0 += nt;
+    if ((int)blockIdx.x >= E * gx1) {
+        const size_t i = (size_t)(blockIdx.x - E * gx1) * 256 + threadIdx.x;
+        if (i >= n2) return;
+        float s = accumulate ? db2[i] : 0.f;
+        for (int k0 = 0; k0 < kColsumSplit; k0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = part2[(size_t)(k0 + u) * n2 + i];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        db2[i] = s;
+        return;
     }
-    if (n >= N) return;
-    const float* src = part + (int64_t)t0 * 2 * N + n;
-    float sum = accumulate ? db[(int64_t)g * N + n] : 0.f;
+    const int g = blockIdx.x / gx1;
+    const int n = (blockIdx.x % gx1) * 256 + threadIdx.x;
+    __shared__ int offs[65];
+    if ((int)threadIdx.x <= E) offs[threadIdx.x] = clamp_pairs(expert_offsets[threadIdx.x], P_cap);
+    __syncthreads();
+    if (n >= N1) return;
+    int t0 = 0;                          // first row tile of expert g
+    for (int e = 0; e < g; ++e) t0 += (offs[e + 1] - offs[e] + BM - 1) / BM;
+    const int nt = (offs[g + 1] - offs[g] + BM - 1) / BM;
+    const float* src = part1 + (int64_t)t0 * 2 * N1 + n;
+    float sum = accumulate ? db1[(int64_t)g * N1 + n] : 0.f;
     int i = 0;
     for (; i + 8 <= 2 * nt; i += 8) {
         float v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(i + u) * N];
+        for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(i + u) * N1];
 #pragma unroll
         for (int u = 0; u < 8; ++u) sum += v[u];
     }
-    for (; i < 2 * nt; ++i) sum += src[(int64_t)i * N];
-    db[(int64_t)g * N + n] = sum;
+    for (; i < 2 * nt; ++i) sum += src[(int64_t)i * N1];
+    db1[(int64_t)g * N1 + n] = sum;
 }
 
 // Tile configurations.  BIG: one block per compute unit, 256 accumulator registers per lane.
@@ -791,11 +808,15 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
     }
     if (err != hipSuccess) return err;
     ProfScope ps(c, EVOMOE_K_FFN_BWD_DB);
-    if (db2) err = launch_colsum<bf16_t>(c, s, dO, s.d, expert_offsets, db2, accumulate, scratch);
+    if (db2) err = launch_colsum_part<bf16_t>(c, s, dO, s.d, expert_offsets, scratch);
     if (err != hipSuccess) return err;
-    if (db1) {
-        hipLaunchKernelGGL(colpart_final_kernel, dim3((s.F + 255) / 256, s.E), dim3(256), 0, c.stream, colpart,
-                           expert_offsets, s.E, s.P_cap, s.F, (int)EVOMOE_CFG_DH::BM, db1, accumulate);
+    if (db1 || db2) {
+        // one launch finishes both: E * gx1 blocks for db1 (if wanted), then gx2 blocks for db2 (if wanted)
+        const size_t n2 = db2 ? (size_t)s.E * s.d : 0;
+        const int gx1 = db1 ? (s.F + 255) / 256 : 0, gx2 = (int)((n2 + 255) / 256);
+        hipLaunchKernelGGL(bias_grad_final_kernel, dim3(s.E * gx1 + gx2), dim3(256), 0, c.stream, colpart,
+                           expert_offsets, s.E, s.P_cap, s.F, (int)EVOMOE_CFG_DH::BM, gx1, db1, scratch, n2, db2,
+                           accumulate);
         err = hipGetLastError();
     }
     return err;

@@ -198,7 +198,6 @@ __global__ __launch_bounds__(256) void ffn_wgrad_kernel(
 // Pass 1: block = 64 columns (8 lanes x 16 bytes) x 32 row lanes, one of kColsumSplit row ranges of one
 // expert; f32 partial sums, tree-reduced over the row lanes in LDS, written to part[split][g][n].
 // Pass 2 adds the splits in order.  No atomics: the result is reproducible bit for bit.
-constexpr int kColsumSplit = 32;
 
 // A block streams whole row segments: CL column lanes x 16 bytes are contiguous in a row (up to 4 KB), RL = 256/CL
 // row lanes take alternate rows, four rows of loads in flight per thread.
@@ -275,8 +274,8 @@ size_t colsum_scratch_bytes(const evomoe_shape& s) {
 }
 
 template <typename TX>
-hipError_t launch_colsum(const Ctx& c, const evomoe_shape& s, const void* Mx, int N,
-                         const int32_t* expert_offsets, float* db, int accumulate, float* scratch) {
+hipError_t launch_colsum_part(const Ctx& c, const evomoe_shape& s, const void* Mx, int N,
+                              const int32_t* expert_offsets, float* scratch) {
     constexpr int KV = Elem<TX>::kVec;
     const int vecs = (N + KV - 1) / KV;                       // 16-byte vectors per row
     int CL = vecs >= 256 ? 256 : vecs;                        // column lanes (contiguous in a row)
@@ -285,6 +284,16 @@ hipError_t launch_colsum(const Ctx& c, const evomoe_shape& s, const void* Mx, in
     hipLaunchKernelGGL(ffn_colsum_part_kernel<TX>, dim3((vecs + CL - 1) / CL, s.E, kColsumSplit), dim3(256),
                        (size_t)RL * CL * KV * sizeof(float), c.stream, (const TX*)Mx, N, s.E, expert_offsets,
                        s.P_cap, CL, scratch);
+    return hipGetLastError();
+}
+template hipError_t launch_colsum_part<float>(const Ctx&, const evomoe_shape&, const void*, int, const int32_t*, float*);
+template hipError_t launch_colsum_part<bf16_t>(const Ctx&, const evomoe_shape&, const void*, int, const int32_t*, float*);
+
+template <typename TX>
+hipError_t launch_colsum(const Ctx& c, const evomoe_shape& s, const void* Mx, int N,
+                         const int32_t* expert_offsets, float* db, int accumulate, float* scratch) {
+    hipError_t err = launch_colsum_part<TX>(c, s, Mx, N, expert_offsets, scratch);
+    if (err != hipSuccess) return err;
     const size_t n = (size_t)s.E * N;
     hipLaunchKernelGGL(ffn_colsum_final_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, scratch, n,
                        db, accumulate);

@@ -452,7 +452,7 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(
     if (blockIdx.y == 0 && threadIdx.x < E) {     // bias gradient partial: sum_s dz[s,e]
         float sb = 0.f;
         for (int s = 0; s < ns; ++s) sb += sdz[s * EP + threadIdx.x];
-        dbg_part[(size_t)chunk * E + threadIdx.x] = sb;
+        dbg_part[(size_t)chunk * (d + 1) * E + threadIdx.x] = sb;
     }
     const int k = (blockIdx.y * 256 + threadIdx.x) * CPT;
     if (k >= d) return;
@@ -514,7 +514,7 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(
     for (int c = 0; c < CPT; ++c)
 #pragma unroll
         for (int e = 0; e < EP; ++e)
-            if (e < E) dWg_part[((size_t)chunk * d + k + c) * E + e] = g[c][e];
+            if (e < E) dWg_part[((size_t)chunk * (d + 1) + k + c) * E + e] = g[c][e];
 }
 
 // ---- bf16 layer: both contractions of the gate backward on the matrix cores ------------------------------
@@ -728,22 +728,25 @@ __global__ __launch_bounds__(256, 2) void gate_bwd_mfma_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int col = c0 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3), e = j * 32 + l32;
-                if (col < d && e < E) dWg_part[((size_t)blk * d + col) * E + e] = acc_w[i][j][r];
+                if (col < d && e < E) dWg_part[((size_t)blk * (d + 1) + col) * E + e] = acc_w[i][j][r];
             }
-    if (slice == 0 && tid < E) dbg_part[(size_t)blk * E + tid] = sb;
+    if (slice == 0 && tid < E) dbg_part[(size_t)blk * (d + 1) * E + tid] = sb;
 }
 
 bool gate_bwd_use_mfma(const evomoe_shape& s) { return s.dtype == EVOMOE_BF16 && s.d % 8 == 0 && s.d >= 8; }
 
 }  // namespace
 
-// out[i] = sum over chunks of part[chunk][i]: four thread groups take a quarter of the chunks each (ascending,
-// 16 independent loads in flight), then the four partial sums are added in group order.  Fixed order: reproducible.
-__global__ __launch_bounds__(256) void sum_chunks_kernel(const float* __restrict__ part, int nchunk,
-                                                         size_t n, float* __restrict__ out)
+// out[i] = sum over chunks of part[chunk][i], i < n0 + n1; the first n0 sums go to out0, the rest to out1 (or
+// nowhere if out1 is null).  Four thread groups take a quarter of the chunks each (ascending, 16 independent loads
+// in flight), then the four partial sums are added in group order.  Fixed order: reproducible.
+__global__ __launch_bounds__(256) void sum_chunks_kernel(const float* __restrict__ part, int nchunk, size_t n0,
+                                                         size_t n1, float* __restrict__ out0,
+                                                         float* __restrict__ out1)
 {
     __shared__ float red[4][64];
     const int o = threadIdx.x & 63, gq = threadIdx.x >> 6;
+    const size_t n = n0 + n1;
     const size_t i = (size_t)blockIdx.x * 64 + o;
     const int per = (nchunk + 3) / 4;
     const int c_lo = gq * per, c_hi = min(nchunk, c_lo + per);
@@ -759,7 +762,11 @@ __global__ __launch_bounds__(256) void sum_chunks_kernel(const float* __restrict
     }
     red[gq][o] = s;
     __syncthreads();
-    if (gq == 0 && i < n) out[i] = ((red[0][o] + red[1][o]) + red[2][o]) + red[3][o];
+    if (gq == 0 && i < n) {
+        const float r = ((red[0][o] + red[1][o]) + red[2][o]) + red[3][o];
+        if (i < n0) out0[i] = r;
+        else if (out1) out1[i - n0] = r;
+    }
 }
 
 static int gate_bwd_chunk_tokens(const evomoe_shape& s) {
@@ -807,7 +814,7 @@ hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float*
     const int nchunk = mfma ? plan.nblk : (s.T + tc - 1) / tc;
     float* dz = (float*)workspace;
     float* dWg_part = dz + (size_t)s.T * s.E;
-    float* dbg_part = dWg_part + (size_t)nchunk * s.d * s.E;
+    float* dbg_part = dWg_part + (size_t)s.d * s.E;     // chunk c: [dWg partial: d x E][dbg partial: E], contiguous
     {
         ProfScope ps(c, EVOMOE_K_GATE_BWD_DZ);
 #define EVOMOE_DZ(EPV)                                                                                   \
@@ -843,13 +850,10 @@ hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float*
         }
     }
     if (err != hipSuccess) return err;
-    const size_t n = (size_t)s.d * s.E;
+    const size_t n0 = (size_t)s.d * s.E, n1 = (size_t)s.E;
     ProfScope ps(c, EVOMOE_K_GATE_BWD_REDUCE);
-    hipLaunchKernelGGL(sum_chunks_kernel, dim3((n + 63) / 64), dim3(256), 0, c.stream, dWg_part,
-                       nchunk, n, dWg);
-    if (dbg)
-        hipLaunchKernelGGL(sum_chunks_kernel, dim3(1), dim3(256), 0, c.stream, dbg_part, nchunk,
-                           (size_t)s.E, dbg);
+    hipLaunchKernelGGL(sum_chunks_kernel, dim3((n0 + n1 + 63) / 64), dim3(256), 0, c.stream, dWg_part, nchunk, n0,
+                       n1, dWg, dbg);
     return hipGetLastError();
 }
 
