@@ -418,20 +418,7 @@ template <int CPT> struct RowVec<float, CPT> {
         else *p = o[0];
     }
 };
-template <int CPT> struct RowVec<bf16_t, CPT> {
-    __device__ static __forceinline__ void load(const bf16_t* p, float* o) {
-        if (CPT == 4) { const u32x2 v = *reinterpret_cast<const u32x2*>(p); o[0] = lo_bf16(v.x); o[1] = hi_bf16(v.x); o[2] = lo_bf16(v.y); o[3] = hi_bf16(v.y); }
-        else if (CPT == 2) { const uint32_t v = *reinterpret_cast<const uint32_t*>(p); o[0] = lo_bf16(v); o[1] = hi_bf16(v); }
-        else o[0] = Elem<bf16_t>::load(p);
-    }
-    __device__ static __forceinline__ void store(bf16_t* p, const float* o) {
-        if (CPT == 4) { const u32x2 v = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])}; *reinterpret_cast<u32x2*>(p) = v; }
-        else if (CPT == 2) { *reinterpret_cast<uint32_t*>(p) = pack_bf16x2(o[0], o[1]); }
-        else Elem<bf16_t>::store(p, o[0]);
-    }
-};
-
-// One block = TC tokens x 256*CPT columns of x.  A thread owns CPT consecutive columns k: it keeps W_g[k,:]
+// float32 layer.  One block = TC tokens x 256*CPT columns of x.  A thread owns CPT consecutive columns k: it keeps W_g[k,:]
 // and a partial dWg[k,:] in registers and walks the chunk's tokens:
 //   dx[s,k] += <dz[s,:], W_g[k,:]>,   dWg_part[k,:] += x[s,k] dz[s,:].
 template <typename TX, int EP, int CPT>
@@ -733,7 +720,7 @@ __global__ __launch_bounds__(256, 2) void gate_bwd_mfma_kernel(
     if (slice == 0 && tid < E) dbg_part[(size_t)blk * (d + 1) * E + tid] = sb;
 }
 
-bool gate_bwd_use_mfma(const evomoe_shape& s) { return s.dtype == EVOMOE_BF16 && s.d % 8 == 0 && s.d >= 8; }
+bool gate_bwd_use_mfma(const evomoe_shape& s) { return s.dtype == EVOMOE_BF16; }   // (d is a multiple of 8 there)
 
 }  // namespace
 
@@ -844,9 +831,7 @@ hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float*
 #undef EVOMOE_GBM
             err = hipGetLastError();
         } else {
-            err = (s.dtype == EVOMOE_BF16)
-                      ? gate_bwd_t<bf16_t>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk)
-                      : gate_bwd_t<float>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk);
+            err = gate_bwd_t<float>(c, s, dz, x, Wg, dx, dWg_part, dbg_part, tc, nchunk);
         }
     }
     if (err != hipSuccess) return err;

@@ -245,3 +245,40 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed():
             for k, v in want.items():
                 assert torch.equal(getattr(b, k), v), f"{k} differs after a graph replay"
             assert torch.equal(b.tok_rows[:P], want_rows)
+
+
+# ---- dispatch on its own: arbitrary masks (not a gate's), many 256-token blocks --------------------
+
+@pytest.mark.parametrize("T,E,density", [(70001, 5, 0.4), (33000, 64, 0.08), (300, 64, 1.0), (1000, 33, 0.0)])
+def test_dispatch_alone_on_random_masks(T, E, density):
+    import torch
+    from oracle import evomoe_oracle as orc
+    from paper_2112_14397_amd import binding as B
+    rng = np.random.default_rng(1234 + T + E)
+    mask = rng.random((T, E)) < density
+    if density == 0.0:
+        mask[7, 3] = True                     # a single pair: every other block and expert is empty
+    scores = rng.random((T, E), dtype=np.float32)
+    bits = np.zeros(T, np.uint64)
+    for e in range(E):
+        bits |= mask[:, e].astype(np.uint64) << np.uint64(e)
+    ref = orc.dispatch(mask, scores)
+    P = int(ref.expert_offsets[E])
+    P_cap = max(P, 1) + 17
+    ctx = B.Context()
+    shape = B.make_shape(T, 64, E, 64, "f32", "relu", P_cap)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    d_bits, d_scores = dev(bits.view(np.int64)), dev(scores)
+    i32 = lambda n: torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    offs, ptok, toff, trows = i32(E + 1), i32(P_cap), i32(T + 1), i32(P_cap)
+    pgate = torch.full((P_cap,), -7.0, dtype=torch.float32, device="cuda")
+    npairs = torch.zeros(1, dtype=torch.int64, device="cuda")
+    for _ in range(2):                        # twice: the context's scratch is reused
+        B.evomoe_dispatch(ctx, shape, d_bits, d_scores, offs, ptok, pgate, toff, trows, npairs)
+    assert B.evomoe_num_pairs(ctx, npairs) == P
+    assert np.array_equal(offs.cpu().numpy(), ref.expert_offsets)
+    assert np.array_equal(toff.cpu().numpy(), ref.tok_off)
+    assert np.array_equal(ptok.cpu().numpy()[:P], ref.pair_token)
+    assert np.array_equal(trows.cpu().numpy()[:P], ref.tok_rows)
+    assert np.array_equal(pgate.cpu().numpy()[:P], ref.pair_gate.astype(np.float32))
+    assert (ptok.cpu().numpy()[P:] == -7).all() and (trows.cpu().numpy()[P:] == -7).all()
