@@ -698,12 +698,18 @@ template <class Cfg> int64_t ctiles(int n) { return (n + Cfg::BN - 1) / Cfg::BN;
 template <class Cfg> int64_t mtiles(int m) { return (m + Cfg::BM - 1) / Cfg::BM; }
 
 #ifndef EVOMOE_CFG_GEMM1
-#define EVOMOE_CFG_GEMM1 CfgDuo
+#define EVOMOE_CFG_GEMM1 CfgBig4
 #define EVOMOE_CFG_GEMM2 CfgBig4
 #define EVOMOE_CFG_DH CfgDuo
 #define EVOMOE_CFG_DX CfgBig4
 #define EVOMOE_CFG_DW CfgBig4
 #endif
+
+// The 256-row tiles pay off when there are enough of them for every compute unit and the experts' row ranges
+// are long enough not to be mostly padding; otherwise the 128-row tiles (two blocks per CU) are used.
+template <class Cfg> bool prefer_small_tiles(const Ctx& c, const evomoe_shape& s, int n) {
+    return row_tiles<Cfg>(s) * ctiles<Cfg>(n) < (int64_t)c.num_cu * 3 / 2 || s.P_cap / s.E < 3 * Cfg::BM;
+}
 
 }  // namespace
 
@@ -725,7 +731,10 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
         a.A = (const bf16_t*)x; a.lda = s.d; a.a_rows = pair_token;
         a.B = (const bf16_t*)W1; a.ldb = s.d; a.b_group_stride = (int64_t)s.F * s.d;
         a.N = s.F; a.K = s.d; a.bias = b1; a.out1 = (bf16_t*)H; a.out2 = (bf16_t*)A;
-        err = launch_gemm<L_NT, E_HA, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.F));
+        if (prefer_small_tiles<Cfg>(c, s, s.F))
+            err = launch_gemm<L_NT, E_HA, CfgDuo>(c, a, row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(s.F));
+        else
+            err = launch_gemm<L_NT, E_HA, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.F));
         if (err != hipSuccess || !O) return err;      // O == nullptr: recomputation of H and A only
     }
     {   // O = A W2^T + b2
@@ -734,8 +743,7 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
         a.A = (const bf16_t*)A; a.lda = s.F; a.a_rows = nullptr;
         a.B = (const bf16_t*)W2; a.ldb = s.F; a.b_group_stride = (int64_t)s.d * s.F;
         a.N = s.d; a.K = s.F; a.bias = b2; a.out1 = (bf16_t*)O; a.out2 = nullptr;
-        // few rows (late in the sweep, Top-1): the big tiles would leave most compute units without a tile
-        if (row_tiles<Cfg>(s) * ctiles<Cfg>(s.d) < (int64_t)c.num_cu * 3 / 2)
+        if (prefer_small_tiles<Cfg>(c, s, s.d))
             err = launch_gemm<L_NT, E_BIAS, CfgDuo>(c, a, row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(s.d));
         else
             err = launch_gemm<L_NT, E_BIAS, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.d));
@@ -770,7 +778,7 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
         a.A = (const bf16_t*)dH; a.lda = s.F; a.B = (const bf16_t*)W1; a.ldb = s.d;
         a.b_group_stride = (int64_t)s.F * s.d; a.N = s.d; a.K = s.F; a.Hin = nullptr;
         a.out1 = (bf16_t*)dXp;
-        if (row_tiles<Cfg>(s) * ctiles<Cfg>(s.d) < (int64_t)c.num_cu * 3 / 2)
+        if (prefer_small_tiles<Cfg>(c, s, s.d))
             err = launch_gemm<L_NN, E_NONE, CfgDuo>(c, a, row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(s.d));
         else
             err = launch_gemm<L_NN, E_NONE, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.d));
