@@ -668,9 +668,12 @@ __global__ __launch_bounds__(256) void bias_grad_final_kernel(
 
 // Tile configurations.  BIG: one block per compute unit, 256 accumulator registers per lane.
 // DUO: two blocks per compute unit (one's epilogue and stalls hide under the other's MFMAs).
+// LAT: for launches with no more tiles than compute units and a long contraction: what counts then is how fast
+// one block walks its K loop, and 64-wide slabs halve the number of load/barrier rounds of that walk.
 struct CfgBig { static constexpr int BM = 256, BN = 256, BK = 64, NSTAGE = 2, WPE = 1; };
 struct CfgDuo { static constexpr int BM = 128, BN = 256, BK = 32, NSTAGE = 3, WPE = 2; };
 struct CfgBig4 { static constexpr int BM = 256, BN = 256, BK = 32, NSTAGE = 4, WPE = 1; };
+struct CfgLat { static constexpr int BM = 128, BN = 256, BK = 64, NSTAGE = 3, WPE = 1; };
 
 template <int LAYOUT, int EPI, class Cfg>
 hipError_t launch_gemm(const Ctx& c, const GemmArgs& a0, int64_t tiles0, const GemmArgs& a1, int64_t tiles1) {
@@ -710,6 +713,10 @@ template <class Cfg> int64_t mtiles(int m) { return (m + Cfg::BM - 1) / Cfg::BM;
 template <class Cfg> bool prefer_small_tiles(const Ctx& c, const evomoe_shape& s, int n) {
     return row_tiles<Cfg>(s) * ctiles<Cfg>(n) < (int64_t)c.num_cu * 3 / 2 || s.P_cap / s.E < 3 * Cfg::BM;
 }
+// ... and among the 128-row configurations: LAT when (about) every tile gets a compute unit of its own
+inline bool prefer_fast_walk(const Ctx& c, const evomoe_shape& s, int n) {
+    return row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(n) <= (int64_t)c.num_cu * 5 / 4;
+}
 
 }  // namespace
 
@@ -743,7 +750,9 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
         a.A = (const bf16_t*)A; a.lda = s.F; a.a_rows = nullptr;
         a.B = (const bf16_t*)W2; a.ldb = s.F; a.b_group_stride = (int64_t)s.d * s.F;
         a.N = s.d; a.K = s.F; a.bias = b2; a.out1 = (bf16_t*)O; a.out2 = nullptr;
-        if (prefer_small_tiles<Cfg>(c, s, s.d))
+        if (prefer_small_tiles<Cfg>(c, s, s.d) && prefer_fast_walk(c, s, s.d))
+            err = launch_gemm<L_NT, E_BIAS, CfgLat>(c, a, row_tiles<CfgLat>(s) * ctiles<CfgLat>(s.d));
+        else if (prefer_small_tiles<Cfg>(c, s, s.d))
             err = launch_gemm<L_NT, E_BIAS, CfgDuo>(c, a, row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(s.d));
         else
             err = launch_gemm<L_NT, E_BIAS, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.d));
@@ -778,7 +787,9 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
         a.A = (const bf16_t*)dH; a.lda = s.F; a.B = (const bf16_t*)W1; a.ldb = s.d;
         a.b_group_stride = (int64_t)s.F * s.d; a.N = s.d; a.K = s.F; a.Hin = nullptr;
         a.out1 = (bf16_t*)dXp;
-        if (prefer_small_tiles<Cfg>(c, s, s.d))
+        if (prefer_small_tiles<Cfg>(c, s, s.d) && prefer_fast_walk(c, s, s.d))
+            err = launch_gemm<L_NN, E_NONE, CfgLat>(c, a, row_tiles<CfgLat>(s) * ctiles<CfgLat>(s.d));
+        else if (prefer_small_tiles<Cfg>(c, s, s.d))
             err = launch_gemm<L_NN, E_NONE, CfgDuo>(c, a, row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(s.d));
         else
             err = launch_gemm<L_NN, E_NONE, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.d));
