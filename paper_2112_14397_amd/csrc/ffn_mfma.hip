@@ -473,6 +473,8 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             KSTEP(fa1, fb1, true, fa0, fb0, slab + 1, 0, L0, L1, slab + NSTAGE - 1);
         };
         int slab = 0;
+        // two blocks per CU: the wave that is feeding the matrix pipe goes ahead of its neighbour's epilogue
+        if (WPE > 1) __builtin_amdgcn_s_setprio(1);
         for (; slab + NSTAGE - 1 < nslab; ++slab) slab_body(slab, std::true_type{});
         for (; slab + 1 < nslab; ++slab) slab_body(slab, std::false_type{});
         if (nslab > 0) {           // last slab: nothing left to fetch or to read ahead
@@ -484,6 +486,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             KSTEP(fa1, fb1, false, fa0, fb0, 0, 0, 0, 0, 0);
         }
 #undef KSTEP
+        if (WPE > 1) __builtin_amdgcn_s_setprio(0);
         block_sync_lds();         // every wave is done reading operands: LDS becomes the epilogue's staging area
 
         // ---------------- epilogue: stage f32 rows through LDS, finish row-major ----------------
