@@ -32,9 +32,9 @@ PEAK_HBM_GBS = 8000.0
 # profiles/ keeps (FETCH_SIZE, WRITE_SIZE; each scaled by what the counter reads for the --copy-probe copy):
 # average over the sweep's temperatures.  None where no such run has been summarised.
 MEASURED_TRAFFIC = {
-    # profiles/layer_gpt_pmc_fetch_size.txt: 426792.7 KiB x 1.9999; profiles/layer_gpt_pmc_write_size.txt:
-    # 152660.8 KiB x 1.0000 (algorithmic: 38969 pairs x (2d + 2F) x 2 B read + 2 x E*d*F x 2 B written = 7.50e8)
-    "gpt": int((426792.7 * 1.9999 + 152660.8 * 1.0) * 1024),
+    # profiles/layer_gpt_pmc_fetch_size.txt: 426303.0 KiB x 1.9999; profiles/layer_gpt_pmc_write_size.txt:
+    # 152617.8 KiB x 1.0000 (algorithmic: 38969 pairs x (2d + 2F) x 2 B read + 2 x E*d*F x 2 B written = 7.50e8)
+    "gpt": int((426303.0 * 1.9999 + 152617.8 * 1.0) * 1024),
 }
 
 

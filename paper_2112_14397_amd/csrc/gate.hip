@@ -323,17 +323,27 @@ __global__ __launch_bounds__(1024) void dts_gate_stream_kernel(
 
     // ---- W_g -> three bf16 terms in LDS (hi + mid + lo carry all 24 mantissa bits) ----
     if (tid < 32) cnt[tid] = 0;
-    for (int i = tid; i < EP * d; i += 1024) {
-        const int e = i % EP, k = i / EP;             // consecutive threads: consecutive experts of one k (as stored)
-        const float w = e < E ? Wg[(size_t)k * E + e] : 0.f;
-        const bf16_t h = (bf16_t)w;
-        const float r1 = w - (float)h;
-        const bf16_t m = (bf16_t)r1;
-        const bf16_t l = (bf16_t)(r1 - (float)m);
-        unsigned char* at = gsm + e * row_bytes + k * 2;
-        *reinterpret_cast<bf16_t*>(at) = h;
-        *reinterpret_cast<bf16_t*>(at + plane_bytes) = m;
-        *reinterpret_cast<bf16_t*>(at + 2 * plane_bytes) = l;
+    for (int i0 = tid; i0 < EP * d; i0 += 8 * 1024) {        // eight loads in flight per thread
+        float w[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * 1024, e = i % EP, k = i / EP;    // consecutive threads: consecutive experts of one k
+            w[u] = (i < EP * d && e < E) ? Wg[(size_t)k * E + e] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * 1024, e = i % EP, k = i / EP;
+            if (i < EP * d) {
+                const bf16_t h = (bf16_t)w[u];
+                const float r1 = w[u] - (float)h;
+                const bf16_t m = (bf16_t)r1;
+                const bf16_t l = (bf16_t)(r1 - (float)m);
+                unsigned char* at = gsm + e * row_bytes + k * 2;
+                *reinterpret_cast<bf16_t*>(at) = h;
+                *reinterpret_cast<bf16_t*>(at + plane_bytes) = m;
+                *reinterpret_cast<bf16_t*>(at + 2 * plane_bytes) = l;
+            }
+        }
     }
     __syncthreads();
 
@@ -341,9 +351,9 @@ __global__ __launch_bounds__(1024) void dts_gate_stream_kernel(
     const int ngr = (nkb + G - 1) / G;                // groups per tile
     const int ntiles = (T + 15) / 16;
     const int nw = gridDim.x * 16;                    // waves in the grid
-    // tiles first, first + nw, ...: with fewer tiles than waves they are spread over the CUs first; otherwise the
-    // sixteen waves of a block take sixteen consecutive tiles (one contiguous 16 x 16 x d stretch of x at a time)
-    const int first = ntiles < nw ? wave * gridDim.x + blockIdx.x : blockIdx.x * 16 + wave;
+    // tiles first, first + nw, ...: the sixteen waves of a block take sixteen consecutive tiles (one contiguous
+    // 16 x 16 x d stretch of x at a time)
+    const int first = blockIdx.x * 16 + wave;
     const int my_tiles = first < ntiles ? (ntiles - first + nw - 1) / nw : 0;
     const int nsteps = my_tiles * ngr;
 
@@ -497,12 +507,16 @@ static size_t gate_stream_lds(const evomoe_shape& s) {
     const size_t ep = s.E <= 16 ? 16 : 32;
     return 3 * ep * ((size_t)s.d * 2 + 16);
 }
-static bool gate_use_stream(const evomoe_shape& s) {
-    return s.dtype == EVOMOE_BF16 && s.E <= 32 && gate_stream_lds(s) <= 150 * 1024;
-}
 static int gate_stream_grid(const Ctx& c, const evomoe_shape& s) {
     const int ntiles = (s.T + 15) / 16;
     return ntiles < c.num_cu ? ntiles : c.num_cu;
+}
+// ... and there is at least one 16-token tile for every wave of the grid (65536 tokens on 256 CUs): with fewer,
+// most waves would idle and a tile's K range would be walked by one wave alone, which the tiled kernel (K split
+// over a block's four waves) does in half the time
+static bool gate_use_stream(const Ctx& c, const evomoe_shape& s) {
+    return s.dtype == EVOMOE_BF16 && s.E <= 32 && gate_stream_lds(s) <= 150 * 1024 &&
+           (s.T + 15) / 16 >= 16 * c.num_cu;
 }
 
 static int pick_rt(const Ctx& c, const evomoe_shape& s) {
@@ -514,7 +528,7 @@ static int pick_rt(const Ctx& c, const evomoe_shape& s) {
 }
 
 int gate_blocks(const Ctx& c, const evomoe_shape& s) {
-    if (gate_use_stream(s)) return gate_stream_grid(c, s);
+    if (gate_use_stream(c, s)) return gate_stream_grid(c, s);
     const int tpb = 16 * pick_rt(c, s);
     return (s.T + tpb - 1) / tpb;
 }
@@ -570,7 +584,7 @@ hipError_t launch_dts_gate(const Ctx& c, const evomoe_shape& s, const void* x, c
                            const float* bg, const float* noise, float tau, float threshold,
                            float* gprime, float* gate_w, uint64_t* mask_bits, int32_t* counts,
                            int32_t* k_per_token) {
-    if (gate_use_stream(s)) {
+    if (gate_use_stream(c, s)) {
         const int grid = gate_stream_grid(c, s);
         const size_t lds = gate_stream_lds(s);
         ProfScope ps(c, EVOMOE_K_GATE);

@@ -282,3 +282,42 @@ def test_dispatch_alone_on_random_masks(T, E, density):
     assert np.array_equal(trows.cpu().numpy()[:P], ref.tok_rows)
     assert np.array_equal(pgate.cpu().numpy()[:P], ref.pair_gate.astype(np.float32))
     assert (ptok.cpu().numpy()[P:] == -7).all() and (trows.cpu().numpy()[P:] == -7).all()
+
+
+# ---- the gate at a token count beyond the configs' (the streaming kernel of bf16 layers with E <= 32) ------
+
+@pytest.mark.parametrize("E,c", [(16, 0.05), (24, 0.03), (7, 0.12)])
+def test_gate_alone_many_tokens(E, c):
+    from oracle import evomoe_oracle as orc
+    from paper_2112_14397_amd import binding as B
+    T, d, tau = 70003, 136, 0.8
+    rng = np.random.default_rng(4321 + E)
+    x = torch.from_numpy(rng.standard_normal((T, d)).astype(np.float32)).to(torch.bfloat16)
+    Wg = (rng.standard_normal((d, E)) * 0.3).astype(np.float32)
+    bg = (rng.standard_normal(E) * 0.1).astype(np.float32)
+    u = rng.random((T, E)).clip(1e-6, 1 - 1e-6)
+    noise = (-np.log(-np.log(u))).astype(np.float32)
+    ref = orc.dts_gate(x.float().numpy().astype(np.float64), Wg, bg, noise, tau, c)
+    ctx = B.Context()
+    shape = B.make_shape(T, d, E, 64, "bf16", "gelu", T * E)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    gp = torch.empty(T, E, dtype=torch.float32, device="cuda")
+    gw = torch.empty(T, E, dtype=torch.float32, device="cuda")
+    mb = torch.zeros(T, dtype=torch.int64, device="cuda")
+    cn = torch.zeros(E, dtype=torch.int32, device="cuda")
+    kt = torch.zeros(T, dtype=torch.int32, device="cuda")
+    B.evomoe_dts_gate(ctx, shape, x.cuda(), dev(Wg), dev(bg), dev(noise), tau, c, gp, gw, mb, cn, kt)
+    g = gp.cpu().numpy()
+    assert np.abs(g - ref.gprime).max() <= 1e-5 * (np.abs(ref.gprime).max() + 1.0)
+    bits = mb.cpu().numpy().view(np.uint64)
+    mask = ((bits[:, None] >> np.arange(E, dtype=np.uint64)[None, :]) & np.uint64(1)).astype(bool)
+    band = np.abs(ref.gprime - c) < 1e-6
+    diff = mask != ref.mask
+    # a token whose scores all sit below c takes its arg-max: its row may differ only if the band touches it
+    rows_band = band.any(axis=1)
+    assert not diff[~rows_band].any(), f"{int(diff[~rows_band].sum())} mask bits differ outside the band"
+    print(f"gate alone E={E}: {int(band.sum())} pairs inside the band, {int(diff.sum())} bits differ (all in band rows)")
+    assert np.array_equal(kt.cpu().numpy(), mask.sum(axis=1))
+    assert np.array_equal(cn.cpu().numpy(), mask.sum(axis=0))
+    w = gw.cpu().numpy()
+    assert np.array_equal(w != 0, mask) and np.array_equal(w[mask], g[mask])
