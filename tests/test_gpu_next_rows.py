@@ -126,3 +126,29 @@ def test_argument_errors_of_the_added_entry_points():
         B.evomoe_expert_ffn(gl.ctx, narrow, gl.x, b.pair_token, b.expert_offsets, gl.params.W1, None, gl.params.W2,
                             None, b.H, b.A, b.O)
     assert e.value.status == B.EVOMOE_EUNSUPPORTED
+
+
+# ---- optional outputs of the FFN backward: any subset gives the same values as the full call ------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ffn_backward_with_some_outputs_left_out(dtype):
+    cfg, inp = small(dtype)
+    gl = H.GpuLayer(inp)
+    gl.forward(0.7, cfg.threshold)
+    gl.backward(0.7)
+    b, p = gl.buf, gl.params
+    full = {n: getattr(b, n).clone() for n in ("dW1", "db1", "dW2", "db2", "dXp")}
+    for keep in (("db1",), ("db2",), ("dW1", "dW2"), ("dW2", "db1"), ()):
+        for n in ("dW1", "db1", "dW2", "db2", "dXp"):
+            getattr(b, n).fill_(float("nan"))
+        arg = lambda n: getattr(b, n) if n in keep else None
+        B.evomoe_expert_ffn_bwd(gl.ctx, gl.shape, b.dO, b.H, b.A, gl.x, b.pair_token, b.expert_offsets, p.W1, p.W2,
+                                arg("dW1"), arg("db1"), arg("dW2"), arg("db2"), b.dXp, False, b.workspace)
+        torch.cuda.synchronize()
+        P = B.evomoe_num_pairs(gl.ctx, b.num_pairs)
+        assert torch.equal(b.dXp[:P], full["dXp"][:P]), f"dXp with {keep}"
+        for n in ("dW1", "db1", "dW2", "db2"):
+            if n in keep:
+                assert torch.equal(getattr(b, n), full[n]), f"{n} with {keep}"
+            else:
+                assert torch.isnan(getattr(b, n).float()).all(), f"{n} was written although it was left out"
