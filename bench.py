@@ -10,13 +10,20 @@ temperature K / len(sweep) times.  Prints ONE JSON line.
 
 The metric is MoE-layer tokens/s forward+backward on the GPT-shaped layer (d=768, E=16, T=8192), with
 the roofline fraction of the dominant kernel (bf16 MFMA) measured live with HIP events, and the CPU oracle
-timed on the host cores on a bounded sample of the same workload as a baseline.
+timed on the host cores on the same workload as a baseline.
+
+After the timed region the same process measures, each labelled in the JSON line: forward and backward
+separately at every temperature (median and minimum over repeats), one supplementary point at threshold 0
+(every expert selected for every token, P = T*E: the dense limit), a per-kernel event table, and the layer
+against the smaller of its two rooflines (bf16 MFMA time of its flops, HBM time of its algorithmic bytes).
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -28,20 +35,36 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel, from the two rocprofv3 --pmc runs of this same command that
-# profiles/ keeps (FETCH_SIZE, WRITE_SIZE; each scaled by what the counter reads for the --copy-probe copy):
-# average over the sweep's temperatures.  None where no such run has been summarised.
-MEASURED_TRAFFIC = {
-    # profiles/layer_gpt_pmc_fetch_size.txt: 426303.0 KiB x 1.9999; profiles/layer_gpt_pmc_write_size.txt:
-    # 152617.8 KiB x 1.0000 (algorithmic: 38969 pairs x (2d + 2F) x 2 B read + 2 x E*d*F x 2 B written = 7.50e8)
-    "gpt": int((426303.0 * 1.9999 + 152617.8 * 1.0) * 1024),
-}
+# the dominant kernel as rocprofv3 names it (the merged weight-gradient launch)
+DOMINANT_PROFILE_NAME = "grouped_gemm_bf16<2, 4,"
 
 
 def _gemm_kernels():
     # expert-FFN GEMM launches and how many 2*P*d*F-flop contractions each carries
     # (ffn_bwd_dw2 is the merged dW2 + dW1 launch; ffn_bwd_dw1 is only the gather of x feeding it)
     return {"ffn_gemm1": 1, "ffn_gemm2": 1, "ffn_bwd_dh": 1, "ffn_bwd_dx": 1, "ffn_bwd_dw2": 2}
+
+
+def profiled_traffic(config):
+    """HBM bytes per launch of the dominant kernel, read from the two rocprofv3 --pmc summaries kept under
+    profiles/ (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the counter reads for a plain
+    copy of known size; both facts are lines of those files).  None when no summary of this config exists."""
+    total = 0.0
+    for counter in ("fetch_size", "write_size"):
+        path = os.path.join(ROOT, "profiles", f"layer_{config}_pmc_{counter}.txt")
+        if not os.path.exists(path):
+            return None
+        kib = scale = None
+        for line in open(path):
+            if line.startswith(DOMINANT_PROFILE_NAME) or (not line.startswith("#") and DOMINANT_PROFILE_NAME in line):
+                kib = float(line.split()[-1])
+            m = re.search(r"true KiB = counter x ([0-9.]+)", line)
+            if m:
+                scale = float(m.group(1))
+        if kib is None or scale is None:
+            return None
+        total += kib * scale * 1024.0
+    return int(total)
 
 
 def cpu_baseline(cfg, inp, n_tokens, taus, top1=False):
@@ -65,9 +88,22 @@ def cpu_baseline(cfg, inp, n_tokens, taus, top1=False):
             orc.balance_loss(fwd.gate, 0.1)
         pairs += int(fwd.disp.expert_offsets[-1])
     dt = time.perf_counter() - t0
+    what = "all" if n_tokens == cfg.T else "the first"
     return {"value": n_tokens * len(taus) / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"first {n_tokens} tokens of the workload, fwd+bwd at each of the {len(taus)} sweep "
+            "sample": f"{what} {n_tokens} tokens of the workload, fwd+bwd at each of the {len(taus)} sweep "
                       f"temperatures ({pairs} pairs, {dt:.1f} s, float64 numpy)"}
+
+
+def layer_bytes(cfg, P):
+    """Algorithmic HBM bytes of one forward + backward pass at P selected pairs: every operand of every step
+    read once and every result written once per step that uses it (weights: four reads and two writes)."""
+    T, d, E, F = cfg.T, cfg.d, cfg.E, cfg.F
+    sz = 2 if cfg.dtype == "bf16" else 4
+    gemm = (6 * P * d + 8 * P * F + 6 * E * d * F) * sz
+    gate = T * (d * sz + E * 8 + 12) + T * 12 + P * 16                      # gate + dispatch
+    stream = (P * d * sz + T * d * sz) * 2 + (2 * P * d * sz + T * d * sz)  # combine, dispatch bwd, combine bwd
+    gate_bwd = T * d * sz * 3 + T * E * 12
+    return gemm + gate + stream + gate_bwd
 
 
 def main():
@@ -83,12 +119,14 @@ def main():
                          "with the balance loss (alpha = 0.1) in the backward")
     ap.add_argument("--recompute", action="store_true",
                     help="backward recomputes the expert activations instead of reading the forward's")
-    ap.add_argument("--cpu-tokens", type=int, default=3072)
+    ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens of the oracle baseline (0 = all of them)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region, run a plain elementwise kernel over 512 MiB three times "
                          "(known traffic each way, to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--no-kernel-table", action="store_true",
-                    help="skip the second pass that times every kernel with events ('kernels' in the JSON)")
+                    help="skip the passes after the timed region (per-temperature forward/backward times, dense "
+                         "limit, per-kernel events)")
+    ap.add_argument("--no-hint", action="store_true", help="do not announce the pair count before each step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (all experts resident, no collectives); "
@@ -98,7 +136,7 @@ def main():
     import numpy as np
     import torch
     from paper_2112_14397_amd import binding as B
-    from paper_2112_14397_amd import synth
+    import synth_inputs as synth
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -136,9 +174,22 @@ def main():
     shape = B.make_shape(cfg.T, cfg.d, cfg.E, cfg.F, cfg.dtype, cfg.act, P_cap)
     buf = B.LayerBuffers(shape, backward=True, recompute=args.recompute)
 
+    # A trainer knows the previous iteration's pair count (evomoe_num_pairs) and the schedule moves it slowly:
+    # it is announced before every step so that the expert GEMMs pick their tile shapes for it, not for P_cap.
+    def hint(tau, P=None):
+        if not args.no_hint:
+            B.evomoe_hint_pairs(ctx, P_of[tau] if P is None else P)
+
+    def fwd(tau, c=cfg.threshold, b=buf):
+        B.layer_forward(ctx, b, params, x, noise, tau, c, write_gate_w=False, top1=top1)
+
+    def bwd(tau, b=buf):
+        B.layer_backward(ctx, b, params, x, dy, tau, balance_alpha=alpha, recompute=args.recompute)
+
     def step(tau):
-        B.layer_forward(ctx, buf, params, x, noise, tau, cfg.threshold, write_gate_w=False, top1=top1)
-        B.layer_backward(ctx, buf, params, x, dy, tau, balance_alpha=alpha, recompute=args.recompute)
+        hint(tau)
+        fwd(tau)
+        bwd(tau)
 
     for i in range(args.warmup):
         step(taus[i % len(taus)])
@@ -166,10 +217,19 @@ def main():
     roofline = {"bound": "mfma", "kernel": dominant + " (grouped_gemm_bf16<2, 4, ...>: dW2 and dW1)",
                 "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA_TFLOPS,
-                "traffic": MEASURED_TRAFFIC.get(args.config),
+                "traffic": None if (top1 or args.recompute) else profiled_traffic(args.config),
                 "avg_launch_us": dom_ms * 1e3 / max(dom_n, 1), "launches": dom_n,
                 "flops_per_launch": "2 GEMMs x 2*P*d*F, P = pairs at the step's temperature "
                                     "(sweep average %.0f)" % (sum(P_steps) / len(P_steps))}
+
+    # the whole layer against the smaller of its two rooflines
+    Pavg = sum(P_steps) / len(P_steps)
+    t_mfma = 6.0 * flops_per_pair_gemm * Pavg / (PEAK_BF16_MFMA_TFLOPS * 1e12)
+    t_hbm = layer_bytes(cfg, Pavg) / (PEAK_HBM_GBS * 1e9)
+    layer_roofline = {"mfma_us": t_mfma * 1e6, "hbm_us": t_hbm * 1e6, "bound": "hbm" if t_hbm > t_mfma else "mfma",
+                      "frac": max(t_mfma, t_hbm) / (ms_per_step * 1e-3),
+                      "note": "time the layer's flops need at the bf16 MFMA peak and its algorithmic bytes at the HBM "
+                              "peak; frac = the larger of the two / measured step time"}
 
     out = {
         "metric": "MoE-layer tokens/s fwd+bwd (d=768,E=16,T=8192) vs tau" if not top1 else
@@ -181,26 +241,60 @@ def main():
                                + (f"c={cfg.threshold}, tau sweep {[round(t, 3) for t in taus]} (one tau per step, cyclic)"
                                   if not top1 else f"Top-1 gate at tau={taus[0]:.3f}, balance loss alpha=0.1")
                                + (", backward recomputes H and A" if args.recompute else ""),
-                   "pairs_per_tau": {f"{t:.3f}": P_of[t] for t in taus}, "P_cap": P_cap},
+                   "pairs_per_tau": {f"{t:.3f}": P_of[t] for t in taus}, "P_cap": P_cap,
+                   "pair_hint": not args.no_hint},
         "layer_tflops": 6.0 * flops_per_pair_gemm * sum(P_steps) / elapsed / 1e12,
         "roofline": roofline,
+        "layer_roofline": layer_roofline,
     }
 
-    # per-temperature throughput (each temperature timed on its own, a few repeats)
-    per_tau = []
-    for tau in taus:
-        for _ in range(2):
-            step(tau)
+    def timed_fwd_bwd(tau, reps, c=cfg.threshold, b=buf):
+        """Forward and backward timed separately with events on the library's stream; (fwd ms, bwd ms) lists."""
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(reps)]
+        for e0, e1, e2 in ev:
+            e0.record()
+            fwd(tau, c, b)
+            e1.record()
+            bwd(tau, b)
+            e2.record()
         torch.cuda.synchronize()
-        reps = 5
-        t1 = time.perf_counter()
-        for _ in range(reps):
-            step(tau)
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t1) * 1e3 / reps
-        per_tau.append({"tau": round(tau, 3), "pairs": P_of[tau], "ms": ms, "tokens_per_s": cfg.T / ms * 1e3,
-                        "tflops": 6.0 * flops_per_pair_gemm * P_of[tau] / ms / 1e9})
-    out["per_tau"] = per_tau
+        return [e0.elapsed_time(e1) for e0, e1, _ in ev], [e1.elapsed_time(e2) for _, e1, e2 in ev]
+
+    def summarize(tau, P, f, g):
+        tot = [a + b for a, b in zip(f, g)]
+        med = statistics.median(tot)
+        return {"tau": round(tau, 3), "pairs": P,
+                "fwd_ms": {"median": statistics.median(f), "min": min(f)},
+                "bwd_ms": {"median": statistics.median(g), "min": min(g)},
+                "ms": med, "ms_min": min(tot), "tokens_per_s": cfg.T / med * 1e3,
+                "tflops": 6.0 * flops_per_pair_gemm * P / med / 1e9}
+
+    if not args.no_kernel_table:
+        # per-temperature throughput: forward and backward timed separately, median and minimum of 20 repeats
+        per_tau = []
+        for tau in taus:
+            hint(tau)
+            for _ in range(5):
+                fwd(tau); bwd(tau)
+            f, g = timed_fwd_bwd(tau, 20)
+            per_tau.append(summarize(tau, P_of[tau], f, g))
+        out["per_tau"] = per_tau
+
+        if not top1 and not args.recompute:
+            # supplementary: the dense limit -- threshold 0, every expert selected for every token (P = T*E)
+            P_dense = cfg.T * cfg.E
+            dshape = B.make_shape(cfg.T, cfg.d, cfg.E, cfg.F, cfg.dtype, cfg.act, P_dense)
+            dbuf = B.LayerBuffers(dshape, backward=True)
+            hint(taus[0], P_dense)
+            for _ in range(3):
+                fwd(taus[0], 0.0, dbuf); bwd(taus[0], dbuf)
+            assert B.evomoe_num_pairs(ctx, dbuf.num_pairs) == P_dense
+            f, g = timed_fwd_bwd(taus[0], 10, 0.0, dbuf)
+            ent = summarize(taus[0], P_dense, f, g)
+            ent["note"] = "supplementary: threshold 0 (all experts selected for every token), not part of the sweep"
+            out["dense_limit"] = ent
+            del dbuf
+            torch.cuda.empty_cache()
 
     if args.copy_probe:
         # a plain elementwise kernel of known traffic: reads 512 MiB, writes 512 MiB (shows up in a kernel
@@ -242,6 +336,7 @@ def main():
             ent = {"avg_us": ms * 1e3 / n, "launches": n}
             if name in _gemm_kernels():
                 ent["tflops"] = _gemm_kernels()[name] * Psum * flops_per_pair_gemm / (ms * 1e-3) / 1e12
+                ent["mfma_frac"] = ent["tflops"] / PEAK_BF16_MFMA_TFLOPS
             if name in stream_bytes:
                 ent["hbm_gbs"] = stream_bytes[name] / (ms * 1e-3 / n) / 1e9
                 ent["hbm_frac"] = ent["hbm_gbs"] / PEAK_HBM_GBS
@@ -249,7 +344,10 @@ def main():
         out["kernels"] = ks
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, inp, min(args.cpu_tokens, cfg.T), taus, top1=top1)
+        n_tok = cfg.T if args.cpu_tokens <= 0 else min(args.cpu_tokens, cfg.T)
+        if args.cpu_tokens <= 0 and args.config in ("mt", "large", "roberta"):
+            n_tok = min(cfg.T, 2048)        # the larger layers: a bounded sample
+        out["cpu_baseline"] = cpu_baseline(cfg, inp, n_tok, taus, top1=top1)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))

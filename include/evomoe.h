@@ -37,8 +37,8 @@
  *  - Limits: 1 <= E <= 64; d and F multiples of 8 (bf16) or 4 (f32);
  *    T*E and P_cap below 2^31 (P_cap*max(d,F) may exceed 2^31: row bases are
  *    64-bit).  The bf16 expert FFN (forward and backward) additionally needs
- *    d >= 64, F >= 64, and T*max(d,F)*2 and d*F*2 below 2^32 bytes (inside a
- *    tile its kernels add 32-bit byte offsets to a 64-bit base).
+ *    d >= 64, F >= 64, T below 2^24, and T*max(d,F)*2 and d*F*2 below 2^32 bytes
+ *    (inside a tile its kernels add 32-bit byte offsets to a 64-bit base).
  */
 #ifndef EVOMOE_H
 #define EVOMOE_H
@@ -89,13 +89,16 @@ size_t evomoe_workspace_bytes(const evomoe_shape* shape);
  *        tau > 0; threshold c >= 0 (the test is strict: g' > c).
  *   out: gprime [T,E] f32 = g'; gate_w [T,E] f32 = g' where selected else 0, NOT renormalised (may be NULL);
  *        mask_bits [T] u64, bit i set <=> expert i selected for the token;
- *        counts [E] i32 = tokens selected per expert; k_per_token [T] i32 (may be NULL).
+ *        counts [E] i32 = tokens selected per expert; k_per_token [T] i32 (may be NULL);
+ *        block_hist [ceil(T/256), E] i32 (may be NULL): row b = tokens selected per expert among tokens
+ *        256 b .. 256 b + 255, the table evomoe_dispatch starts from (handing it over saves that call a pass
+ *        over mask_bits).
  * A token with no score above c keeps its arg-max expert (lowest index on ties), so 1 <= k_s <= E. */
 evomoe_status evomoe_dts_gate(evomoe_ctx* ctx, const evomoe_shape* shape,
                               const void* x, const float* Wg, const float* bg, const float* noise,
                               float tau, float threshold,
                               float* gprime, float* gate_w, uint64_t* mask_bits,
-                              int32_t* counts, int32_t* k_per_token);
+                              int32_t* counts, int32_t* k_per_token, int32_t* block_hist);
 
 /* Top-1 branch of the DTS gate (Algorithm 2, else-branch: iterations >= T_D; "switch to Top1" in the
  * temperature-scheduler study).  Same inputs and outputs as evomoe_dts_gate without a threshold: every
@@ -106,7 +109,7 @@ evomoe_status evomoe_dts_gate_top1(evomoe_ctx* ctx, const evomoe_shape* shape,
                                    const void* x, const float* Wg, const float* bg, const float* noise,
                                    float tau,
                                    float* gprime, float* gate_w, uint64_t* mask_bits,
-                                   int32_t* counts, int32_t* k_per_token);
+                                   int32_t* counts, int32_t* k_per_token, int32_t* block_hist);
 
 /* Balance loss (Eq. balance_loss):  L = alpha * N * sum_i (count_i / T^2) * sum_s g'_si,
  * and its gradient with respect to g'_si, which is the same for every token: coef_i = alpha * N * count_i / T^2
@@ -120,7 +123,9 @@ evomoe_status evomoe_balance_loss(evomoe_ctx* ctx, const evomoe_shape* shape,
 
 /* Dispatch (Algorithm 1: the loop over id in id_s, turned into a permutation).  Stable counting
  * sort of the selected pairs: expert-major, token-ascending.
- *   in : mask_bits [T]; scores [T,E] f32 (g' or gate_w: only selected entries are read).
+ *   in : mask_bits [T] (bits of experts >= E are ignored); scores [T,E] f32 (g' or gate_w: only selected entries
+ *        are read); block_hist (last argument) [ceil(T/256), E] i32 as written by the gate for THIS mask_bits, or
+ *        NULL (the call then counts the table itself; a table that does not match mask_bits gives wrong rows).
  *   out: expert_offsets [E+1] i32 (row range of expert i is [off[i], off[i+1]); off[E] = P);
  *        pair_token [P_cap] i32 (token of row r); pair_gate [P_cap] f32 (its weight G);
  *        tok_off [T+1] i32 and tok_rows [P_cap] i32: token s owns rows tok_rows[tok_off[s] .. tok_off[s+1])
@@ -130,7 +135,7 @@ evomoe_status evomoe_dispatch(evomoe_ctx* ctx, const evomoe_shape* shape,
                               const uint64_t* mask_bits, const float* scores,
                               int32_t* expert_offsets, int32_t* pair_token, float* pair_gate,
                               int32_t* tok_off, int32_t* tok_rows, int64_t* num_pairs,
-                              const void* x, void* x_perm);
+                              const void* x, void* x_perm, const int32_t* block_hist);
 
 /* Expert FFNs forward over the ragged per-expert row ranges (Eq. ffn per expert e_i : R^D -> R^D).
  *   in : x [T,d] elem gathered through pair_token [P_cap], or, if pair_token == NULL, x is already
@@ -149,7 +154,9 @@ evomoe_status evomoe_combine(evomoe_ctx* ctx, const evomoe_shape* shape,
                              const void* O, const float* pair_gate,
                              const int32_t* tok_off, const int32_t* tok_rows, void* y);
 
-/* Backward of combine:  dO[r,:] = pair_gate[r] * dy[pair_token[r],:];  dG_pairs[r] = <dy[pair_token[r],:], O[r,:]>.
+/* Backward of combine (the derivative of Eq. moe_weighted_sum_problem, y_s = sum_r G_r O_r, with respect to each
+ * expert output and each weight; the paper derives no backward):
+ *   dO[r,:] = pair_gate[r] * dy[pair_token[r],:];  dG_pairs[r] = <dy[pair_token[r],:], O[r,:]>.
  *   in : dy [T,d] elem, O, pair_gate, pair_token, expert_offsets (for P).  out: dO [P_cap,d] elem, dG_pairs [P_cap] f32. */
 evomoe_status evomoe_combine_bwd(evomoe_ctx* ctx, const evomoe_shape* shape,
                                  const void* dy, const void* O, const float* pair_gate,
@@ -159,7 +166,11 @@ evomoe_status evomoe_combine_bwd(evomoe_ctx* ctx, const evomoe_shape* shape,
 /* Backward of the expert FFNs (calculus on Eq. ffn; the paper derives none):
  *   db2_i = sum_rows dO;  dW2_i = dO_i^T A_i;  dA = dO_i W2_i;  dH = dA * act'(H);
  *   db1_i = sum_rows dH;  dW1_i = dH_i^T X_i;  dXp = dH W1_i.
- *   in : dO [P_cap,d], H, A [P_cap,F], x / pair_token as in the forward, expert_offsets, W1, W2.
+ *   in : dO [P_cap,d], H, A [P_cap,F], x / pair_token as in the forward, expert_offsets, W1, W2;
+ *        dy [T,d] elem and pair_gate [P_cap] f32, optional (both or neither; need pair_token): the inputs dO was
+ *        made from, dO[r,:] = pair_gate[r] * dy[pair_token[r],:].  When given, a bf16 layer evaluates
+ *        dA = pair_gate[r] * (dy[pair_token[r],:] W2_i) with the weight applied in float32, so that the bf16
+ *        rounding of the stored dO stays out of dH, dXp, dW1 and db1 (dW2 and db2 are sums over dO itself).
  *   out: dW1 [E,F,d] elem, db1 [E,F] f32, dW2 [E,d,F] elem, db2 [E,d] f32 (each may be NULL to skip),
  *        dXp [P_cap,d] elem (gradient w.r.t. each row's input).
  *   accumulate != 0 adds the weight/bias gradients to the buffers' current contents.
@@ -168,15 +179,19 @@ evomoe_status evomoe_expert_ffn_bwd(evomoe_ctx* ctx, const evomoe_shape* shape,
                                     const void* dO, const void* H, const void* A,
                                     const void* x, const int32_t* pair_token, const int32_t* expert_offsets,
                                     const void* W1, const void* W2,
+                                    const void* dy, const float* pair_gate,
                                     void* dW1, float* db1, void* dW2, float* db2, void* dXp,
                                     int accumulate, void* workspace, size_t workspace_bytes);
 
-/* Backward of dispatch: dx[s,:] = sum of dXp over the token's rows (ascending expert, f32 accumulate).
+/* Backward of dispatch (Algorithm 1's loop over id in id_s hands x_s to each of the token's experts, so the
+ * token's input gradient is the sum over them): dx[s,:] = sum of dXp over the token's rows (ascending expert,
+ * f32 accumulate).
  *   out: dx [T,d] elem (overwritten). */
 evomoe_status evomoe_dispatch_bwd(evomoe_ctx* ctx, const evomoe_shape* shape,
                                   const void* dXp, const int32_t* tok_off, const int32_t* tok_rows, void* dx);
 
-/* Backward of the DTS gate, selection treated as a constant:
+/* Backward of the DTS gate: the derivative of Eq. gumbel_softmax (temperature softmax of x W_g + b_g + zeta)
+ * followed by Eq. adaptive_sparsity, whose 0/1 selection is treated as a constant:
  *   dG_si = dG_pairs at the token's selected experts, 0 elsewhere;
  *   dz_sj = (g'_sj / tau) * (dG_sj - sum_i dG_si g'_si);  dWg = x^T dz;  dbg = sum_s dz_s;  dx_s += W_g dz_s.
  * Unselected experts' columns of W_g receive gradient through the softmax normaliser.
@@ -206,13 +221,15 @@ evomoe_status evomoe_dts_gate_bwd_balance(evomoe_ctx* ctx, const evomoe_shape* s
  * counterpart of the paper's MoE-aware recomputation, Implementation section): H and A are recomputed from x
  * by the forward's first GEMM into the workspace, then the backward proceeds as evomoe_expert_ffn_bwd.
  * Costs 14*d*F instead of 12*d*F flop per pair over forward + backward and saves 2*P_cap*F elements of
- * resident activations.  Arguments as evomoe_expert_ffn_bwd without H and A, plus b1.
+ * resident activations.  Arguments as evomoe_expert_ffn_bwd without H and A, plus b1 (dy and pair_gate optional,
+ * as there).
  *   workspace: at least evomoe_workspace_bytes_recompute(shape) bytes. */
 size_t evomoe_workspace_bytes_recompute(const evomoe_shape* shape);
 evomoe_status evomoe_expert_ffn_bwd_recompute(evomoe_ctx* ctx, const evomoe_shape* shape,
                                               const void* dO,
                                               const void* x, const int32_t* pair_token, const int32_t* expert_offsets,
                                               const void* W1, const float* b1, const void* W2,
+                                              const void* dy, const float* pair_gate,
                                               void* dW1, float* db1, void* dW2, float* db2, void* dXp,
                                               int accumulate, void* workspace, size_t workspace_bytes);
 
@@ -228,8 +245,30 @@ typedef struct {
 evomoe_status evomoe_schedule(int64_t iteration, int64_t T_S, int64_t T_D, float tau_hi, float tau_lo,
                               evomoe_phase* phase_out);
 
+/* Expert-diversify (Stage 1 "Expert-Diversify"; Algorithm 1, the loop e_i <- diversify(e, i)): spawns the E experts
+ * of the layer from the one shared expert by setting a random part of its weights to 0, a different part for each
+ * expert.  The paper gives neither the masked fraction nor the random source: mask_ratio in [0,1] is the probability
+ * with which each weight of W1 and W2 is masked, independently; biases are copied unmasked.  The random numbers are
+ * counter-based, so the result depends only on (seed, mask_ratio): weight number j (row-major) of tensor t (0 = W1,
+ * 1 = W2) of expert i is masked when the top 24 bits of output number (t << 62 | i << 48 | j) of the SplitMix64
+ * sequence seeded with `seed` are below floor(mask_ratio * 2^24).
+ *   in : W1_shared [F,d] elem, b1_shared [F] f32 (may be NULL), W2_shared [d,F] elem, b2_shared [d] f32 (may be NULL).
+ *   out: W1 [E,F,d] elem, b1 [E,F] f32 (NULL iff b1_shared is), W2 [E,d,F] elem, b2 [E,d] f32 (NULL iff b2_shared is).
+ * T and P_cap of the shape are not used. */
+evomoe_status evomoe_diversify(evomoe_ctx* ctx, const evomoe_shape* shape,
+                               const void* W1_shared, const float* b1_shared,
+                               const void* W2_shared, const float* b2_shared,
+                               uint64_t seed, float mask_ratio,
+                               void* W1, float* b1, void* W2, float* b2);
+
 /* Copies P to the host and reports a pending capacity overflow.  The only synchronising call. */
 evomoe_status evomoe_num_pairs(evomoe_ctx* ctx, const int64_t* num_pairs, int64_t* num_pairs_host);
+
+/* Host only, no device work.  Announces the number of selected pairs the next calls will see (for instance the
+ * previous iteration's evomoe_num_pairs: the Sparsity Scheduler changes P slowly).  The expert-FFN calls pick
+ * their tile shapes for that many rows instead of for P_cap rows; results do not depend on it, buffers and
+ * launch grids stay sized for P_cap.  expected_pairs <= 0 withdraws the announcement. */
+evomoe_status evomoe_hint_pairs(evomoe_ctx* ctx, int64_t expected_pairs);
 
 /* ---- measurement aid (not part of the layer) ----------------------------------------------------
  * Times kernels with HIP events recorded around their launches on the context's own stream.
@@ -242,7 +281,7 @@ typedef enum {
     EVOMOE_K_FFN_GEMM2, EVOMOE_K_COMBINE, EVOMOE_K_COMBINE_BWD, EVOMOE_K_FFN_BWD_DH,
     EVOMOE_K_FFN_BWD_DX, EVOMOE_K_FFN_BWD_DW2, EVOMOE_K_FFN_BWD_DW1, EVOMOE_K_FFN_BWD_DB,
     EVOMOE_K_DISPATCH_BWD, EVOMOE_K_GATE_BWD_DZ, EVOMOE_K_GATE_BWD_MAIN, EVOMOE_K_GATE_BWD_REDUCE,
-    EVOMOE_K_BALANCE_LOSS,
+    EVOMOE_K_BALANCE_LOSS, EVOMOE_K_DIVERSIFY,
     EVOMOE_K_COUNT, EVOMOE_K_ALL = -2, EVOMOE_K_NONE = -1
 } evomoe_kernel_id;
 evomoe_status evomoe_profile_select(evomoe_ctx* ctx, int kernel_id);

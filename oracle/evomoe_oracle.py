@@ -28,7 +28,9 @@ example, the E=2 sigmoid closed form, the dense (tau->inf, c=0) and top-1
 (tau->0) limits, textbook values of Phi, a literal per-token brute force of
 Algorithm 1, torch-CPU float64 autograd of an all-experts formulation, and
 central finite differences; the balance loss and its gradient by a closed form,
-finite differences and autograd; the schedule by the paper's quoted step counts.
+finite differences and autograd; the schedule by the paper's quoted step counts;
+the diversify masks by the published SplitMix64 test vectors, the two limits of
+the mask ratio and binomial bounds on the masked fraction.
 No function here is "parity unpinned".
 """
 from __future__ import annotations
@@ -402,3 +404,54 @@ def schedule(iteration, T_S, T_D, tau_hi=2.0, tau_lo=0.3) -> Phase:
         tau = tau_hi if T_D == 1 else tau_hi - (tau_hi - tau_lo) * (j / F64(T_D - 1))
         return Phase(2, False, float(tau))
     return Phase(2, True, float(tau_lo))
+
+
+# ---------------------------------------------------------------------------
+# Expert-diversify (Stage 1; Algorithm 1's loop  e_i <- diversify(e, i))
+# ---------------------------------------------------------------------------
+# The paper spawns the N experts from the one shared expert by a random mask
+# that sets part of its weights to 0, a different mask per expert; it gives
+# neither the masked fraction nor the random source.  Readings taken here: the
+# fraction is an argument; every weight of W1 and W2 is masked independently
+# with that probability; biases are copied unmasked; the random numbers come
+# from a counter-based generator, so that both sides can draw the same ones:
+# weight number j of tensor t (0 = W1, 1 = W2) of expert i uses output number
+# (t << 62 | i << 48 | j) of the SplitMix64 sequence (Steele, Lea & Flood 2014;
+# Vigna's public-domain constants) seeded with `seed`, and is masked when the
+# top 24 bits of that output are below floor(ratio * 2^24).
+
+_U64 = np.uint64
+
+
+def splitmix64_output(seed, n):
+    """Output number n (0-based, scalar or uint64 array) of the SplitMix64 sequence seeded with `seed`."""
+    with np.errstate(over="ignore"):
+        z = _U64(seed) + (np.asarray(n, _U64) + _U64(1)) * _U64(0x9E3779B97F4A7C15)
+        z = (z ^ (z >> _U64(30))) * _U64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> _U64(27))) * _U64(0x94D049BB133111EB)
+        return z ^ (z >> _U64(31))
+
+
+def diversify_keep_mask(seed, mask_ratio, tensor, expert, n_weights):
+    """bool [n_weights]: True where expert `expert` keeps weight j of tensor `tensor` (0 = W1, 1 = W2)."""
+    limit = int(np.floor(np.float64(np.float32(mask_ratio)) * 2.0 ** 24))      # the caller passes a float32
+    ctr = (_U64(tensor) << _U64(62)) | (_U64(expert) << _U64(48)) | np.arange(n_weights, dtype=_U64)
+    return (splitmix64_output(seed, ctr) >> _U64(40)).astype(np.int64) >= limit
+
+
+def diversify(W1_shared, b1_shared, W2_shared, b2_shared, E, seed, mask_ratio):
+    """e_i <- diversify(e, i) for i = 0..E-1: copies of the shared expert (W1 [F,d], b1 [F], W2 [d,F], b2 [d])
+    with a different random part of the weights set to 0 in each.  Returns W1 [E,F,d], b1 [E,F], W2 [E,d,F],
+    b2 [E,d] in the dtype of the inputs."""
+    W1_shared = np.asarray(W1_shared)
+    W2_shared = np.asarray(W2_shared)
+    W1 = np.empty((E,) + W1_shared.shape, W1_shared.dtype)
+    W2 = np.empty((E,) + W2_shared.shape, W2_shared.dtype)
+    for i in range(E):
+        keep1 = diversify_keep_mask(seed, mask_ratio, 0, i, W1_shared.size).reshape(W1_shared.shape)
+        keep2 = diversify_keep_mask(seed, mask_ratio, 1, i, W2_shared.size).reshape(W2_shared.shape)
+        W1[i] = np.where(keep1, W1_shared, 0)
+        W2[i] = np.where(keep2, W2_shared, 0)
+    b1 = np.repeat(np.asarray(b1_shared)[None, :], E, axis=0)
+    b2 = np.repeat(np.asarray(b2_shared)[None, :], E, axis=0)
+    return W1, b1, W2, b2

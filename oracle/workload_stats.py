@@ -10,7 +10,7 @@ import time
 import numpy as np
 
 from oracle import evomoe_oracle as orc
-from paper_2112_14397_amd import synth
+import synth_inputs as synth
 
 
 def main(names):

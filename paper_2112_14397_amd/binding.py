@@ -27,11 +27,12 @@ ENTRY_POINTS = (
     "evomoe_num_pairs", "evomoe_profile_select", "evomoe_profile_read",
     "evomoe_dts_gate_top1", "evomoe_balance_loss", "evomoe_dts_gate_bwd_balance",
     "evomoe_workspace_bytes_recompute", "evomoe_expert_ffn_bwd_recompute", "evomoe_schedule",
+    "evomoe_hint_pairs", "evomoe_diversify",
 )
 
 KERNEL_IDS = ("gate", "dispatch_hist", "dispatch_scatter", "ffn_gemm1", "ffn_gemm2", "combine", "combine_bwd",
               "ffn_bwd_dh", "ffn_bwd_dx", "ffn_bwd_dw2", "ffn_bwd_dw1", "ffn_bwd_db", "dispatch_bwd",
-              "gate_bwd_dz", "gate_bwd_main", "gate_bwd_reduce", "balance_loss")
+              "gate_bwd_dz", "gate_bwd_main", "gate_bwd_reduce", "balance_loss", "diversify")
 EVOMOE_K_ALL, EVOMOE_K_NONE = -2, -1
 
 
@@ -70,21 +71,23 @@ def lib() -> ctypes.CDLL:
         L.evomoe_status_string.restype = ctypes.c_char_p
         L.evomoe_workspace_bytes.argtypes = [sp]
         L.evomoe_workspace_bytes.restype = sz
-        L.evomoe_dts_gate.argtypes = [vp, sp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp, vp]
-        L.evomoe_dispatch.argtypes = [vp, sp] + [vp] * 10
+        L.evomoe_dts_gate.argtypes = [vp, sp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp, vp, vp]
+        L.evomoe_dispatch.argtypes = [vp, sp] + [vp] * 11
         L.evomoe_expert_ffn.argtypes = [vp, sp] + [vp] * 10
         L.evomoe_combine.argtypes = [vp, sp] + [vp] * 5
         L.evomoe_combine_bwd.argtypes = [vp, sp] + [vp] * 7
-        L.evomoe_expert_ffn_bwd.argtypes = [vp, sp] + [vp] * 13 + [i32, vp, sz]
+        L.evomoe_expert_ffn_bwd.argtypes = [vp, sp] + [vp] * 15 + [i32, vp, sz]
         L.evomoe_dispatch_bwd.argtypes = [vp, sp] + [vp] * 4
         L.evomoe_dts_gate_bwd.argtypes = [vp, sp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, vp, sz]
         L.evomoe_num_pairs.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int64)]
-        L.evomoe_dts_gate_top1.argtypes = [vp, sp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
+        L.evomoe_dts_gate_top1.argtypes = [vp, sp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, vp]
         L.evomoe_balance_loss.argtypes = [vp, sp, vp, vp, f32, vp, vp]
         L.evomoe_dts_gate_bwd_balance.argtypes = [vp, sp, vp, vp, vp, vp, vp, f32, vp, vp, vp, f32, vp, vp, vp, vp, sz]
         L.evomoe_workspace_bytes_recompute.argtypes = [sp]
         L.evomoe_workspace_bytes_recompute.restype = sz
-        L.evomoe_expert_ffn_bwd_recompute.argtypes = [vp, sp] + [vp] * 12 + [i32, vp, sz]
+        L.evomoe_expert_ffn_bwd_recompute.argtypes = [vp, sp] + [vp] * 14 + [i32, vp, sz]
+        L.evomoe_hint_pairs.argtypes = [vp, ctypes.c_int64]
+        L.evomoe_diversify.argtypes = [vp, sp, vp, vp, vp, vp, ctypes.c_uint64, f32, vp, vp, vp, vp]
         L.evomoe_schedule.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, f32, f32, ctypes.POINTER(Phase)]
         L.evomoe_profile_select.argtypes = [vp, i32]
         L.evomoe_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
@@ -143,16 +146,18 @@ def evomoe_workspace_bytes(shape: Shape) -> int:
     return int(lib().evomoe_workspace_bytes(ctypes.byref(shape)))
 
 
-def evomoe_dts_gate(ctx, shape, x, Wg, bg, noise, tau, threshold, gprime, gate_w, mask_bits, counts, k_per_token):
+def evomoe_dts_gate(ctx, shape, x, Wg, bg, noise, tau, threshold, gprime, gate_w, mask_bits, counts, k_per_token,
+                    block_hist=None):
     _chk(lib().evomoe_dts_gate(ctx._h, ctypes.byref(shape), _p(x), _p(Wg), _p(bg), _p(noise), tau, threshold,
-                               _p(gprime), _p(gate_w), _p(mask_bits), _p(counts), _p(k_per_token)), "evomoe_dts_gate")
+                               _p(gprime), _p(gate_w), _p(mask_bits), _p(counts), _p(k_per_token), _p(block_hist)),
+         "evomoe_dts_gate")
 
 
 def evomoe_dispatch(ctx, shape, mask_bits, scores, expert_offsets, pair_token, pair_gate, tok_off, tok_rows,
-                    num_pairs, x=None, x_perm=None):
+                    num_pairs, x=None, x_perm=None, block_hist=None):
     _chk(lib().evomoe_dispatch(ctx._h, ctypes.byref(shape), _p(mask_bits), _p(scores), _p(expert_offsets),
                                _p(pair_token), _p(pair_gate), _p(tok_off), _p(tok_rows), _p(num_pairs),
-                               _p(x), _p(x_perm)), "evomoe_dispatch")
+                               _p(x), _p(x_perm), _p(block_hist)), "evomoe_dispatch")
 
 
 def evomoe_expert_ffn(ctx, shape, x, pair_token, expert_offsets, W1, b1, W2, b2, H, A, O):
@@ -170,10 +175,11 @@ def evomoe_combine_bwd(ctx, shape, dy, O, pair_gate, pair_token, expert_offsets,
                                   _p(expert_offsets), _p(dO), _p(dG_pairs)), "evomoe_combine_bwd")
 
 
-def evomoe_expert_ffn_bwd(ctx, shape, dO, H, A, x, pair_token, expert_offsets, W1, W2, dW1, db1, dW2, db2, dXp,
-                          accumulate, workspace):
+def evomoe_expert_ffn_bwd(ctx, shape, dO, H, A, x, pair_token, expert_offsets, W1, W2, dy, pair_gate, dW1, db1, dW2,
+                          db2, dXp, accumulate, workspace):
     _chk(lib().evomoe_expert_ffn_bwd(ctx._h, ctypes.byref(shape), _p(dO), _p(H), _p(A), _p(x), _p(pair_token),
-                                     _p(expert_offsets), _p(W1), _p(W2), _p(dW1), _p(db1), _p(dW2), _p(db2),
+                                     _p(expert_offsets), _p(W1), _p(W2), _p(dy), _p(pair_gate), _p(dW1), _p(db1),
+                                     _p(dW2), _p(db2),
                                      _p(dXp), int(accumulate), _p(workspace),
                                      workspace.numel() * workspace.element_size()), "evomoe_expert_ffn_bwd")
 
@@ -191,10 +197,11 @@ def evomoe_dts_gate_bwd(ctx, shape, dG_pairs, tok_off, tok_rows, gprime, mask_bi
          "evomoe_dts_gate_bwd")
 
 
-def evomoe_dts_gate_top1(ctx, shape, x, Wg, bg, noise, tau, gprime, gate_w, mask_bits, counts, k_per_token):
+def evomoe_dts_gate_top1(ctx, shape, x, Wg, bg, noise, tau, gprime, gate_w, mask_bits, counts, k_per_token,
+                         block_hist=None):
     _chk(lib().evomoe_dts_gate_top1(ctx._h, ctypes.byref(shape), _p(x), _p(Wg), _p(bg), _p(noise), tau,
-                                    _p(gprime), _p(gate_w), _p(mask_bits), _p(counts), _p(k_per_token)),
-         "evomoe_dts_gate_top1")
+                                    _p(gprime), _p(gate_w), _p(mask_bits), _p(counts), _p(k_per_token),
+                                    _p(block_hist)), "evomoe_dts_gate_top1")
 
 
 def evomoe_balance_loss(ctx, shape, gprime, counts, alpha, loss, dgprime_coef):
@@ -215,10 +222,11 @@ def evomoe_workspace_bytes_recompute(shape: Shape) -> int:
     return int(lib().evomoe_workspace_bytes_recompute(ctypes.byref(shape)))
 
 
-def evomoe_expert_ffn_bwd_recompute(ctx, shape, dO, x, pair_token, expert_offsets, W1, b1, W2, dW1, db1, dW2, db2,
-                                    dXp, accumulate, workspace):
+def evomoe_expert_ffn_bwd_recompute(ctx, shape, dO, x, pair_token, expert_offsets, W1, b1, W2, dy, pair_gate, dW1,
+                                    db1, dW2, db2, dXp, accumulate, workspace):
     _chk(lib().evomoe_expert_ffn_bwd_recompute(ctx._h, ctypes.byref(shape), _p(dO), _p(x), _p(pair_token),
-                                               _p(expert_offsets), _p(W1), _p(b1), _p(W2), _p(dW1), _p(db1),
+                                               _p(expert_offsets), _p(W1), _p(b1), _p(W2), _p(dy), _p(pair_gate),
+                                               _p(dW1), _p(db1),
                                                _p(dW2), _p(db2), _p(dXp), int(accumulate), _p(workspace),
                                                workspace.numel() * workspace.element_size()),
          "evomoe_expert_ffn_bwd_recompute")
@@ -228,6 +236,16 @@ def evomoe_schedule(iteration, T_S, T_D, tau_hi=2.0, tau_lo=0.3) -> Phase:
     ph = Phase()
     _chk(lib().evomoe_schedule(iteration, T_S, T_D, tau_hi, tau_lo, ctypes.byref(ph)), "evomoe_schedule")
     return ph
+
+
+def evomoe_diversify(ctx, shape, W1_shared, b1_shared, W2_shared, b2_shared, seed, mask_ratio, W1, b1, W2, b2):
+    _chk(lib().evomoe_diversify(ctx._h, ctypes.byref(shape), _p(W1_shared), _p(b1_shared), _p(W2_shared),
+                                _p(b2_shared), int(seed), float(mask_ratio), _p(W1), _p(b1), _p(W2), _p(b2)),
+         "evomoe_diversify")
+
+
+def evomoe_hint_pairs(ctx, expected_pairs: int) -> None:
+    _chk(lib().evomoe_hint_pairs(ctx._h, int(expected_pairs)), "evomoe_hint_pairs")
 
 
 def evomoe_num_pairs(ctx, num_pairs) -> int:
@@ -276,7 +294,7 @@ class LayerBuffers:
         self.mask_bits = z(T, dtype=i64); self.counts = z(E, dtype=i32); self.k = z(T, dtype=i32)
         self.expert_offsets = z(E + 1, dtype=i32); self.pair_token = z(P, dtype=i32)
         self.pair_gate = z(P, dtype=f32); self.tok_off = z(T + 1, dtype=i32); self.tok_rows = z(P, dtype=i32)
-        self.num_pairs = z(1, dtype=i64)
+        self.num_pairs = z(1, dtype=i64); self.block_hist = z((T + 255) // 256, E, dtype=i32)
         self.H = z(P, F); self.A = z(P, F); self.O = z(P, d); self.y = z(T, d)
         if backward:
             self.dO = z(P, d); self.dG_pairs = z(P, dtype=f32); self.dXp = z(P, d); self.dx = z(T, d)
@@ -291,12 +309,12 @@ def layer_forward(ctx, b: LayerBuffers, p: LayerParams, x, noise, tau, threshold
     s = b.shape
     if top1:
         evomoe_dts_gate_top1(ctx, s, x, p.Wg, p.bg, noise, tau, b.gprime, b.gate_w if write_gate_w else None,
-                             b.mask_bits, b.counts, b.k)
+                             b.mask_bits, b.counts, b.k, b.block_hist)
     else:
         evomoe_dts_gate(ctx, s, x, p.Wg, p.bg, noise, tau, threshold, b.gprime, b.gate_w if write_gate_w else None,
-                        b.mask_bits, b.counts, b.k)
+                        b.mask_bits, b.counts, b.k, b.block_hist)
     evomoe_dispatch(ctx, s, b.mask_bits, b.gprime, b.expert_offsets, b.pair_token, b.pair_gate, b.tok_off,
-                    b.tok_rows, b.num_pairs)
+                    b.tok_rows, b.num_pairs, block_hist=b.block_hist)
     evomoe_expert_ffn(ctx, s, x, b.pair_token, b.expert_offsets, p.W1, p.b1, p.W2, p.b2, b.H, b.A, b.O)
     evomoe_combine(ctx, s, b.O, b.pair_gate, b.tok_off, b.tok_rows, b.y)
 
@@ -310,10 +328,10 @@ def layer_backward(ctx, b: LayerBuffers, p: LayerParams, x, dy, tau, accumulate=
     evomoe_combine_bwd(ctx, s, dy, b.O, b.pair_gate, b.pair_token, b.expert_offsets, b.dO, b.dG_pairs)
     if recompute:
         evomoe_expert_ffn_bwd_recompute(ctx, s, b.dO, x, b.pair_token, b.expert_offsets, p.W1, p.b1, p.W2,
-                                        b.dW1, b.db1, b.dW2, b.db2, b.dXp, accumulate, b.workspace)
+                                        dy, b.pair_gate, b.dW1, b.db1, b.dW2, b.db2, b.dXp, accumulate, b.workspace)
     else:
         evomoe_expert_ffn_bwd(ctx, s, b.dO, b.H, b.A, x, b.pair_token, b.expert_offsets, p.W1, p.W2,
-                              b.dW1, b.db1, b.dW2, b.db2, b.dXp, accumulate, b.workspace)
+                              dy, b.pair_gate, b.dW1, b.db1, b.dW2, b.db2, b.dXp, accumulate, b.workspace)
     evomoe_dispatch_bwd(ctx, s, b.dXp, b.tok_off, b.tok_rows, b.dx)
     if balance_alpha is not None:
         evomoe_balance_loss(ctx, s, b.gprime, b.counts, float(balance_alpha), b.bal_loss, b.bal_coef)

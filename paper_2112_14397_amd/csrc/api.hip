@@ -30,7 +30,7 @@ evomoe_status check_shape(const evomoe_shape* s) {
 evomoe_status check_ffn_shape(const evomoe_shape* s) {
     if (s->dtype != EVOMOE_BF16) return EVOMOE_OK;
     const int64_t lim = (int64_t)1 << 32, wide = s->d > s->F ? s->d : s->F;
-    if (s->d < 64 || s->F < 64) return EVOMOE_EUNSUPPORTED;
+    if (s->d < 64 || s->F < 64 || s->T >= (1 << 24)) return EVOMOE_EUNSUPPORTED;
     if ((int64_t)s->T * wide * 2 >= lim || (int64_t)s->d * s->F * 2 >= lim) return EVOMOE_EUNSUPPORTED;
     return EVOMOE_OK;
 }
@@ -95,6 +95,7 @@ evomoe_status evomoe_create(evomoe_ctx** ctx_out, void* hip_stream) {
     c.wg_planes_bytes = 0;
     c.status_dev = nullptr;
     c.prof = nullptr;
+    c.pair_hint = 0;
     hipDeviceProp_t prop;
     int32_t* small = nullptr;
     if (hipGetDevice(&c.device) != hipSuccess || hipGetDeviceProperties(&prop, c.device) != hipSuccess ||
@@ -154,29 +155,27 @@ size_t evomoe_workspace_bytes(const evomoe_shape* shape) {
 evomoe_status evomoe_dts_gate(evomoe_ctx* ctx, const evomoe_shape* shape, const void* x,
                               const float* Wg, const float* bg, const float* noise, float tau,
                               float threshold, float* gprime, float* gate_w, uint64_t* mask_bits,
-                              int32_t* counts, int32_t* k_per_token) {
+                              int32_t* counts, int32_t* k_per_token, int32_t* block_hist) {
     CHECK_CTX_SHAPE();
     REQUIRE_PTR(x); REQUIRE_PTR(Wg); REQUIRE_PTR(gprime); REQUIRE_PTR(mask_bits); REQUIRE_PTR(counts);
-    OPTIONAL_PTR(bg); OPTIONAL_PTR(noise); OPTIONAL_PTR(gate_w); OPTIONAL_PTR(k_per_token);
+    OPTIONAL_PTR(bg); OPTIONAL_PTR(noise); OPTIONAL_PTR(gate_w); OPTIONAL_PTR(k_per_token); OPTIONAL_PTR(block_hist);
     if (!(tau > 0.f) || !(threshold >= 0.f)) return EVOMOE_EINVAL;
-    evomoe_status st = ensure_scratch(ctx->c, (size_t)gate_blocks(ctx->c, *shape) * shape->E);
-    if (st != EVOMOE_OK) return st;
     if (shape->dtype == EVOMOE_BF16) {
-        st = ensure_wg_planes(ctx->c, (size_t)3 * 64 * shape->d * sizeof(uint16_t));
+        evomoe_status st = ensure_wg_planes(ctx->c, (size_t)3 * 64 * shape->d * sizeof(uint16_t));
         if (st != EVOMOE_OK) return st;
     }
     return from_hip(launch_dts_gate(ctx->c, *shape, x, Wg, bg, noise, tau, threshold, gprime, gate_w,
-                                    mask_bits, counts, k_per_token));
+                                    mask_bits, counts, k_per_token, block_hist));
 }
 
 evomoe_status evomoe_dts_gate_top1(evomoe_ctx* ctx, const evomoe_shape* shape, const void* x,
                                    const float* Wg, const float* bg, const float* noise, float tau,
                                    float* gprime, float* gate_w, uint64_t* mask_bits, int32_t* counts,
-                                   int32_t* k_per_token) {
+                                   int32_t* k_per_token, int32_t* block_hist) {
     // No score exceeds a threshold above 1, so every token takes the arg-max rule of the threshold gate
     // (lowest index on ties): exactly Algorithm 2's Top-1 branch, with the un-renormalised weight g'.
     return evomoe_dts_gate(ctx, shape, x, Wg, bg, noise, tau, 2.0f, gprime, gate_w, mask_bits, counts,
-                           k_per_token);
+                           k_per_token, block_hist);
 }
 
 evomoe_status evomoe_balance_loss(evomoe_ctx* ctx, const evomoe_shape* shape, const float* gprime,
@@ -191,18 +190,20 @@ evomoe_status evomoe_balance_loss(evomoe_ctx* ctx, const evomoe_shape* shape, co
 }
 
 evomoe_status evomoe_dispatch(evomoe_ctx* ctx, const evomoe_shape* shape, const uint64_t* mask_bits,
-                              const float* scores, int32_t* expert_offsets, int32_t* pair_token,
-                              float* pair_gate, int32_t* tok_off, int32_t* tok_rows,
-                              int64_t* num_pairs, const void* x, void* x_perm) {
+                              const float* scores, int32_t* expert_offsets,
+                              int32_t* pair_token, float* pair_gate, int32_t* tok_off, int32_t* tok_rows,
+                              int64_t* num_pairs, const void* x, void* x_perm, const int32_t* block_hist) {
     CHECK_CTX_SHAPE();
     REQUIRE_PTR(mask_bits); REQUIRE_PTR(scores); REQUIRE_PTR(expert_offsets); REQUIRE_PTR(pair_token);
     REQUIRE_PTR(pair_gate); REQUIRE_PTR(tok_off); REQUIRE_PTR(tok_rows); REQUIRE_PTR(num_pairs);
-    OPTIONAL_PTR(x); OPTIONAL_PTR(x_perm);
+    OPTIONAL_PTR(x); OPTIONAL_PTR(x_perm); OPTIONAL_PTR(block_hist);
     if (x_perm && !x) return EVOMOE_EINVAL;
-    const size_t nblk = dispatch_blocks(*shape);
-    evomoe_status st = ensure_scratch(ctx->c, nblk * shape->E + nblk);
-    if (st != EVOMOE_OK) return st;
-    return from_hip(launch_dispatch(ctx->c, *shape, mask_bits, scores, expert_offsets, pair_token,
+    if (!block_hist) {
+        const size_t nblk = dispatch_blocks(*shape);
+        evomoe_status st = ensure_scratch(ctx->c, nblk * shape->E + nblk);
+        if (st != EVOMOE_OK) return st;
+    }
+    return from_hip(launch_dispatch(ctx->c, *shape, mask_bits, scores, block_hist, expert_offsets, pair_token,
                                     pair_gate, tok_off, tok_rows, num_pairs, x, x_perm));
 }
 
@@ -238,7 +239,8 @@ evomoe_status evomoe_combine_bwd(evomoe_ctx* ctx, const evomoe_shape* shape, con
 evomoe_status evomoe_expert_ffn_bwd(evomoe_ctx* ctx, const evomoe_shape* shape, const void* dO,
                                     const void* H, const void* A, const void* x,
                                     const int32_t* pair_token, const int32_t* expert_offsets,
-                                    const void* W1, const void* W2, void* dW1, float* db1, void* dW2,
+                                    const void* W1, const void* W2, const void* dy, const float* pair_gate,
+                                    void* dW1, float* db1, void* dW2,
                                     float* db2, void* dXp, int accumulate, void* workspace,
                                     size_t workspace_bytes) {
     CHECK_CTX_SHAPE();
@@ -246,10 +248,12 @@ evomoe_status evomoe_expert_ffn_bwd(evomoe_ctx* ctx, const evomoe_shape* shape, 
     REQUIRE_PTR(dO); REQUIRE_PTR(H); REQUIRE_PTR(A); REQUIRE_PTR(x); REQUIRE_PTR(expert_offsets);
     REQUIRE_PTR(W1); REQUIRE_PTR(W2); REQUIRE_PTR(dXp);
     OPTIONAL_PTR(pair_token); OPTIONAL_PTR(dW1); OPTIONAL_PTR(db1); OPTIONAL_PTR(dW2); OPTIONAL_PTR(db2);
+    OPTIONAL_PTR(dy); OPTIONAL_PTR(pair_gate);
+    if ((dy != nullptr) != (pair_gate != nullptr) || (dy && !pair_token)) return EVOMOE_EINVAL;
     if (!workspace || !aligned16(workspace) || workspace_bytes < ffn_bwd_workspace_bytes(*shape))
         return EVOMOE_EWORKSPACE;
     return from_hip(launch_expert_ffn_bwd(ctx->c, *shape, dO, H, A, x, pair_token, expert_offsets, W1,
-                                          W2, dW1, db1, dW2, db2, dXp, accumulate, workspace));
+                                          W2, dy, pair_gate, dW1, db1, dW2, db2, dXp, accumulate, workspace));
 }
 
 evomoe_status evomoe_dispatch_bwd(evomoe_ctx* ctx, const evomoe_shape* shape, const void* dXp,
@@ -302,19 +306,23 @@ size_t evomoe_workspace_bytes_recompute(const evomoe_shape* shape) {
 evomoe_status evomoe_expert_ffn_bwd_recompute(evomoe_ctx* ctx, const evomoe_shape* shape, const void* dO,
                                               const void* x, const int32_t* pair_token,
                                               const int32_t* expert_offsets, const void* W1, const float* b1,
-                                              const void* W2, void* dW1, float* db1, void* dW2, float* db2,
+                                              const void* W2, const void* dy, const float* pair_gate,
+                                              void* dW1, float* db1, void* dW2, float* db2,
                                               void* dXp, int accumulate, void* workspace,
                                               size_t workspace_bytes) {
     CHECK_CTX_SHAPE();
     if (evomoe_status fs = check_ffn_shape(shape); fs != EVOMOE_OK) return fs;
     REQUIRE_PTR(dO); REQUIRE_PTR(x); REQUIRE_PTR(expert_offsets); REQUIRE_PTR(W1); REQUIRE_PTR(W2);
     REQUIRE_PTR(dXp);
+    OPTIONAL_PTR(dy); OPTIONAL_PTR(pair_gate);
+    if ((dy != nullptr) != (pair_gate != nullptr) || (dy && !pair_token)) return EVOMOE_EINVAL;
     OPTIONAL_PTR(pair_token); OPTIONAL_PTR(b1); OPTIONAL_PTR(dW1); OPTIONAL_PTR(db1); OPTIONAL_PTR(dW2);
     OPTIONAL_PTR(db2);
     if (!workspace || !aligned16(workspace) || workspace_bytes < ffn_bwd_recompute_workspace_bytes(*shape))
         return EVOMOE_EWORKSPACE;
     return from_hip(launch_expert_ffn_bwd_recompute(ctx->c, *shape, dO, x, pair_token, expert_offsets, W1, b1,
-                                                    W2, dW1, db1, dW2, db2, dXp, accumulate, workspace));
+                                                    W2, dy, pair_gate, dW1, db1, dW2, db2, dXp, accumulate,
+                                                    workspace));
 }
 
 evomoe_status evomoe_schedule(int64_t iteration, int64_t T_S, int64_t T_D, float tau_hi, float tau_lo,
@@ -349,6 +357,25 @@ evomoe_status evomoe_num_pairs(evomoe_ctx* ctx, const int64_t* num_pairs, int64_
         if (hipMemsetAsync(ctx->c.status_dev, 0, sizeof(int32_t), ctx->c.stream) != hipSuccess) return EVOMOE_EHIP;
         return EVOMOE_ECAPACITY;
     }
+    return EVOMOE_OK;
+}
+
+evomoe_status evomoe_diversify(evomoe_ctx* ctx, const evomoe_shape* shape, const void* W1_shared,
+                               const float* b1_shared, const void* W2_shared, const float* b2_shared,
+                               uint64_t seed, float mask_ratio, void* W1, float* b1, void* W2, float* b2) {
+    CHECK_CTX_SHAPE();
+    REQUIRE_PTR(W1_shared); REQUIRE_PTR(W2_shared); REQUIRE_PTR(W1); REQUIRE_PTR(W2);
+    OPTIONAL_PTR(b1_shared); OPTIONAL_PTR(b2_shared); OPTIONAL_PTR(b1); OPTIONAL_PTR(b2);
+    if ((b1_shared != nullptr) != (b1 != nullptr) || (b2_shared != nullptr) != (b2 != nullptr)) return EVOMOE_EINVAL;
+    if (!(mask_ratio >= 0.f) || !(mask_ratio <= 1.f)) return EVOMOE_EINVAL;
+    if ((int64_t)shape->d * shape->F >= ((int64_t)1 << 48)) return EVOMOE_EUNSUPPORTED;
+    return from_hip(launch_diversify(ctx->c, *shape, W1_shared, b1_shared, W2_shared, b2_shared, seed, mask_ratio,
+                                     W1, b1, W2, b2));
+}
+
+evomoe_status evomoe_hint_pairs(evomoe_ctx* ctx, int64_t expected_pairs) {
+    if (!ctx) return EVOMOE_EINVAL;
+    ctx->c.pair_hint = expected_pairs > 0 ? expected_pairs : 0;
     return EVOMOE_OK;
 }
 

@@ -102,6 +102,7 @@ struct Ctx {
     hipStream_t stream;
     int device;
     int num_cu;
+    int64_t pair_hint;        // pair count announced by the caller (0 = none): picks tile shapes, nothing else
     int32_t* status_dev;      // [1] device flag: bit0 = capacity overflow
     int32_t* block_counts;    // scratch for per-block expert histograms
     size_t block_counts_elems;

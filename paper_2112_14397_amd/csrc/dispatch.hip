@@ -15,7 +15,8 @@ __global__ __launch_bounds__(256) void dispatch_hist_kernel(
     __shared__ int wc[4][64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int t = blockIdx.x * kDispatchTokens + tid;
-    const uint64_t bits = (t < T) ? mask_bits[t] : 0ull;
+    const uint64_t valid = E >= 64 ? ~0ull : (1ull << E) - 1ull;      // bits of experts that do not exist are ignored
+    const uint64_t bits = (t < T) ? (mask_bits[t] & valid) : 0ull;
     for (int e = 0; e < E; ++e) {
         const uint64_t bal = __ballot((bits >> e) & 1ull);
         if (lane == 0) wc[wave][e] = __popcll(bal);
@@ -48,7 +49,8 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
     __shared__ int tok_base_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int t = blockIdx.x * kDispatchTokens + tid;
-    const uint64_t bits = (t < T) ? mask_bits[t] : 0ull;
+    const uint64_t valid = E >= 64 ? ~0ull : (1ull << E) - 1ull;      // bits of experts that do not exist are ignored
+    const uint64_t bits = (t < T) ? (mask_bits[t] & valid) : 0ull;
     const uint64_t lt = (1ull << lane) - 1ull;
 
     // ---- the block's share of the scan ----
@@ -172,14 +174,16 @@ hipError_t launch_gather_rows(const Ctx& c, const evomoe_shape& s, const void* x
 }
 
 hipError_t launch_dispatch(const Ctx& c, const evomoe_shape& s, const uint64_t* mask_bits,
-                           const float* scores, int32_t* expert_offsets, int32_t* pair_token,
-                           float* pair_gate, int32_t* tok_off, int32_t* tok_rows, int64_t* num_pairs,
-                           const void* x, void* x_perm) {
+                           const float* scores, const int32_t* block_hist, int32_t* expert_offsets,
+                           int32_t* pair_token, float* pair_gate, int32_t* tok_off, int32_t* tok_rows,
+                           int64_t* num_pairs, const void* x, void* x_perm) {
     const int nblk = dispatch_blocks(s);
-    int32_t* table = c.block_counts;
-    {
+    const int32_t* table = block_hist;
+    if (!table) {       // the per-block histograms did not come with the mask: count them here
         ProfScope ps(c, EVOMOE_K_DISPATCH_HIST);
-        hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, s.T, s.E, table);
+        hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, s.T, s.E,
+                           c.block_counts);
+        table = c.block_counts;
     }
     {
         ProfScope ps(c, EVOMOE_K_DISPATCH_SCATTER);

@@ -20,11 +20,12 @@ hipError_t launch_expert_ffn(const Ctx& c, const evomoe_shape& s, const void* x,
 hipError_t launch_expert_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, const void* H,
                                  const void* A, const void* x, const int32_t* pair_token,
                                  const int32_t* expert_offsets, const void* W1, const void* W2,
+                                 const void* dy, const float* pair_gate,
                                  void* dW1, float* db1, void* dW2, float* db2, void* dXp,
                                  int accumulate, void* workspace) {
     if (s.dtype == EVOMOE_BF16)
-        return mfma_ffn_bwd(c, s, dO, H, A, x, pair_token, expert_offsets, W1, W2, dW1, db1, dW2, db2,
-                            dXp, accumulate, workspace);
+        return mfma_ffn_bwd(c, s, dO, H, A, x, pair_token, expert_offsets, W1, W2, dy, pair_gate, dW1, db1,
+                            dW2, db2, dXp, accumulate, workspace);
     return simple_ffn_bwd<float>(c, s, dO, H, A, x, pair_token, expert_offsets, W1, W2, dW1, db1, dW2,
                                  db2, dXp, accumulate, workspace);
 }
@@ -36,7 +37,8 @@ size_t ffn_bwd_recompute_workspace_bytes(const evomoe_shape& s) {
 }
 hipError_t launch_expert_ffn_bwd_recompute(const Ctx& c, const evomoe_shape& s, const void* dO, const void* x,
                                            const int32_t* pair_token, const int32_t* expert_offsets,
-                                           const void* W1, const float* b1, const void* W2, void* dW1,
+                                           const void* W1, const float* b1, const void* W2, const void* dy,
+                                           const float* pair_gate, void* dW1,
                                            float* db1, void* dW2, float* db2, void* dXp, int accumulate,
                                            void* workspace) {
     char* w = static_cast<char*>(workspace);
@@ -45,8 +47,8 @@ hipError_t launch_expert_ffn_bwd_recompute(const Ctx& c, const evomoe_shape& s, 
     void* rest = w + 2 * act_bytes(s);
     hipError_t err = launch_expert_ffn(c, s, x, pair_token, expert_offsets, W1, b1, W2, nullptr, H, A, nullptr);
     if (err != hipSuccess) return err;
-    return launch_expert_ffn_bwd(c, s, dO, H, A, x, pair_token, expert_offsets, W1, W2, dW1, db1, dW2, db2,
-                                 dXp, accumulate, rest);
+    return launch_expert_ffn_bwd(c, s, dO, H, A, x, pair_token, expert_offsets, W1, W2, dy, pair_gate, dW1, db1,
+                                 dW2, db2, dXp, accumulate, rest);
 }
 
 }  // namespace evomoe

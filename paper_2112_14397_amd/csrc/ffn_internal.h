@@ -37,7 +37,7 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
                         const float* b2, void* H, void* A, void* O);
 hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, const void* H, const void* A,
                         const void* x, const int32_t* pair_token, const int32_t* expert_offsets,
-                        const void* W1, const void* W2, void* dW1, float* db1, void* dW2, float* db2,
-                        void* dXp, int accumulate, void* dH);
+                        const void* W1, const void* W2, const void* dy, const float* pair_gate, void* dW1,
+                        float* db1, void* dW2, float* db2, void* dXp, int accumulate, void* dH);
 
 }  // namespace evomoe

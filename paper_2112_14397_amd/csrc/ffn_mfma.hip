@@ -38,6 +38,7 @@ struct GemmArgs {
     int M, N, K;                        // M: TN only.  K: NT/NN only (TN contracts over the expert's rows)
     const float* bias;                  // [E,N] or null
     const bf16_t* Hin;                  // E_ACTGRAD: pre-activations [P,N]
+    const float* row_scale;             // E_ACTGRAD: per-row factor applied in f32 before act' (or null)
     bf16_t* out1;                       // C (H for E_HA)
     bf16_t* out2;                       // E_HA: A = act(H)
     float* colpart;                     // E_ACTGRAD: per-tile column sums of C, [row tile][2][N] (or null)
@@ -66,14 +67,14 @@ template <int LAYOUT, int BM, int BN, int BK, int NSTAGE> struct Geo {
     static constexpr int EPI_ROWS = (WM >= 64 && 4 * 64 * EPI_LD * 4 <= NSTAGE * STAGE + 8192) ? 64 : 32;
     static constexpr int EPI_BYTES = 4 * EPI_ROWS * EPI_LD * 4;
     static constexpr int MAIN = (NSTAGE * STAGE > EPI_BYTES ? NSTAGE * STAGE : EPI_BYTES);
-    static constexpr int SMEM = MAIN + 1024;                 // + landing area of the L2 prefetch loads
+    static constexpr int SMEM = MAIN;
 };
 
-// Phi(h), the standard normal CDF, as 0.5 + h*Q(h^2) on |h| <= 4.2 (clamped beyond): degree-8 minimax
+// Phi(h), the standard normal CDF, as 0.5 + hc*Q(hc^2) with hc = h clamped to |h| <= 4.2: degree-8 minimax
 // fit of Q, |error| < 1.2e-5 -- below the resolution of the bf16 values it is multiplied into -- and no
 // transcendental.  gelu(h) = h*Phi(h);  gelu'(h) = Phi(h) + h*phi(h).
-__device__ __forceinline__ float phi_cdf(float h, float& u) {
-    const float hc = __builtin_amdgcn_fmed3f(h, -4.2f, 4.2f);
+__device__ __forceinline__ float phi_cdf(float h, float& hc, float& u) {
+    hc = __builtin_amdgcn_fmed3f(h, -4.2f, 4.2f);
     u = hc * hc;
     float q = 5.998071484e-11f;
     q = fmaf(q, u, -5.633320033e-09f);
@@ -86,17 +87,21 @@ __device__ __forceinline__ float phi_cdf(float h, float& u) {
     q = fmaf(q, u, 3.989074528e-01f);
     return fmaf(hc, q, 0.5f);
 }
+// Beyond the fitted range the values stay within 2.5e-4 of the true ones for any h: gelu(h) -> h for large h
+// (Phi(4.2) = 1 - 1.3e-5) and -> max(h, -4.2) * 1.3e-5 for very negative h; gelu'(h) is evaluated at hc, where it
+// has reached its limits 1 and 0 to 2.4e-4.
 __device__ __forceinline__ float act_fwd_fast(float h, int act) {
     if (act == EVOMOE_RELU) return h > 0.f ? h : 0.f;
-    float u;
-    return h * phi_cdf(h, u);
+    float hc, u;
+    const float Phi = phi_cdf(h, hc, u);
+    return fmaxf(h, -4.2f) * Phi;
 }
 __device__ __forceinline__ float act_grad_fast(float h, int act) {
     if (act == EVOMOE_RELU) return h > 0.f ? 1.f : 0.f;
-    float u;
-    const float Phi = phi_cdf(h, u);
+    float hc, u;
+    const float Phi = phi_cdf(h, hc, u);
     const float dens = 0.39894228040143267794f * __builtin_amdgcn_exp2f(u * -0.72134752044448170368f);
-    return fmaf(h, dens, Phi);         // beyond the clamp both terms are < 1e-3 of their limits
+    return fmaf(hc, dens, Phi);
 }
 
 // 16 bytes per lane, global -> LDS, no registers in between: lane l's data lands at lds + 16*l.
@@ -116,10 +121,6 @@ __device__ __forceinline__ void store_out(bf16_t* p, const float* in) {
 __device__ __forceinline__ void load_to_lds(const unsigned char* base, uint32_t voff, const unsigned char* lds_wave_base) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(voff), "s"(base), "s"(lds_addr(lds_wave_base)) : "m0", "memory");
-}
-__device__ __forceinline__ void touch_to_lds(const bf16_t* gptr, const unsigned char* lds_wave_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-                 :: "v"(gptr), "s"(lds_addr(lds_wave_base)) : "m0", "memory");
 }
 // Block barrier that orders LDS traffic only (global loads in flight stay in flight).
 __device__ __forceinline__ void block_sync_lds() {
@@ -144,13 +145,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
     constexpr int A_CPR = BM / 8, A_RPI = 64 / A_CPR;        // k-strided A: 16 B chunks per k-row, k-rows per instruction
     constexpr int B_CPR = BN / 8, B_RPI = 64 / B_CPR;
     constexpr int NMF = TM * TN_, NFR = TM + TN_, NLD = A_LD + B_LD;
-    // L2 prefetch (one block per CU only): the streamed operand's lines of a slab PFD slabs beyond the one
-    // being loaded are touched with 4-byte loads, so that the 16-byte loads later hit in L2 instead of
-    // waiting for HBM with only NSTAGE-1 slabs of cover.
-    constexpr bool PF = (WPE == 1 && BK == 64 && BM == 256);
-    constexpr int PFD = 2;
-    constexpr int NPF = !PF ? 0 : (LAYOUT == L_TN ? 2 : 1);
-    constexpr bool SPLIT_LD = NSTAGE >= 3 && !PF;   // half of a slab's loads before the barrier, half after
+    constexpr bool SPLIT_LD = NSTAGE >= 3;          // half of a slab's loads before the barrier, half after
     static_assert(BK == 32 || BK == 64, "slab");
     static_assert(WM % 32 == 0 && WN % 32 == 0 && A_LD >= 1 && B_LD >= 1 && NSTAGE >= 2 && KS % 2 == 0, "tile");
     static_assert((NSTAGE - 2) * NLD + (NSTAGE - 1) * 2 <= 63, "vmcnt range");
@@ -295,31 +290,6 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
         const int klen = kend - kbeg;
         const int kc_lim = 2 * (kend - 8 - kc_chunk * 8);        // k-contiguous: last in-range chunk start (bytes)
         const uint32_t lda2 = (uint32_t)p.lda * 2, ldb2 = (uint32_t)p.ldb * 2;
-        // prefetch addresses: k-contiguous A: thread = tile row (one 128 B line per row and slab);
-        // k-strided (TN): thread = (k-row tid/4, 128 B segment tid%4) of the 64 x 512 B slab
-        const bf16_t* pf_a = p.A;
-        const bf16_t* pf_b = p.B;
-        if (PF) {
-            if (G::A_KC) {
-                const int r = min(tid, rows - 1);
-                pf_a = p.A + (p.a_rows ? (int64_t)p.a_rows[row0 + r] : (int64_t)(row0 + r)) * p.lda;
-            } else {
-                pf_a = p.A + min(m0 + (tid & 3) * 64, p.M - 8);
-                pf_b = p.B + min(n0 + (tid & 3) * 64, p.N - 8);
-            }
-        }
-        auto prefetch = [&](int slab) {
-            if (!PF) return;
-            unsigned char* sink = smem + G::MAIN + wave * 256;
-            const int sl = min(slab, nslab - 1);
-            if (G::A_KC) {
-                touch_to_lds(pf_a + min(sl * BK, kend - 8), sink);
-            } else {
-                const int64_t r = min(kbeg + sl * BK + (tid >> 2), kend - 1);
-                touch_to_lds(pf_a + r * p.lda, sink);
-                touch_to_lds(pf_b + r * p.ldb, sink);
-            }
-        };
         // issue load instruction `idx` (A: 0..A_LD-1, then B) of slab `slab` into its stage; addresses
         // are clamped into the contraction range (a no-op except in the last, partial slab)
         auto issue_one = [&](int idx, int slab) {
@@ -437,9 +407,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             for (int s = 0; s < NSTAGE - 1; ++s) {
                 if (s < nslab) issue(s);
             }
-#pragma unroll
-            for (int s = NSTAGE - 1; s < NSTAGE - 1 + PFD; ++s) prefetch(s);
-            if (nslab >= NSTAGE - 1 && NPF == 0) wait_vmcnt<(NSTAGE - 2) * NLD>(); else wait_vmcnt<0>();
+            if (nslab >= NSTAGE - 1) wait_vmcnt<(NSTAGE - 2) * NLD>(); else wait_vmcnt<0>();
             block_sync_lds();
             if (nslab == 1 && ragged) {
                 zero_tail();
@@ -458,13 +426,12 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             // (its stage was released one slab earlier), which keeps the load unit evenly busy
             constexpr int L0 = !LOADS ? 0 : (SPLIT_LD ? NLD / 2 : NLD), L1 = LOADS ? NLD : 0;
             KSTEP(fa0, fb0, true, fa1, fb1, slab, 1, 0, L0, slab + NSTAGE - 1);
-            if (LOADS) prefetch(slab + NSTAGE - 1 + PFD);
             if (KS == 4) {
                 KSTEP(fa1, fb1, true, fa0, fb0, slab, 2, 0, 0, 0);
                 KSTEP(fa0, fb0, true, fa1, fb1, slab, 3, 0, 0, 0);
             }
             // everything issued after slab+1's loads may still be in flight
-            if (LOADS) wait_vmcnt<(NSTAGE - 2) * NLD - (NLD - L0) + (NSTAGE - 1) * NPF>(); else wait_vmcnt<0>();
+            if (LOADS) wait_vmcnt<(NSTAGE - 2) * NLD - (NLD - L0)>(); else wait_vmcnt<0>();
             block_sync_lds();
             if (slab + 2 == nslab && ragged) {
                 zero_tail();
@@ -522,11 +489,13 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
 #pragma unroll
         for (int pass = 0; pass < WM / ER; ++pass) {
             u32x4 hraw[EPI == E_ACTGRAD ? NIT : 1];
+            float rsc[EPI == E_ACTGRAD ? NIT : 1];
             if (EPI == E_ACTGRAD) {
 #pragma unroll
                 for (int it = 0; it < NIT; ++it) {
                     const int trow = min(wm * WM + pass * ER + it * RPI + lane / CPW, rows - 1);
                     hraw[it] = *reinterpret_cast<const u32x4*>(p.Hin + (int64_t)(row0 + trow) * p.N + col_c);
+                    rsc[it] = p.row_scale ? p.row_scale[row0 + trow] : 1.f;
                 }
             }
 #pragma unroll
@@ -576,12 +545,13 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
                         const float h[8] = {lo_bf16(hw.x), hi_bf16(hw.x), lo_bf16(hw.y), hi_bf16(hw.y),
                                             lo_bf16(hw.z), hi_bf16(hw.z), lo_bf16(hw.w), hi_bf16(hw.w)};
                         // one branch per eight values (not per value): the eight polynomial chains interleave
+                        const float sc = rsc[it];
                         if (p.act == EVOMOE_RELU) {
 #pragma unroll
-                            for (int q = 0; q < 8; ++q) v[q] *= act_grad_fast(h[q], EVOMOE_RELU);
+                            for (int q = 0; q < 8; ++q) v[q] *= sc * act_grad_fast(h[q], EVOMOE_RELU);
                         } else {
 #pragma unroll
-                            for (int q = 0; q < 8; ++q) v[q] *= act_grad_fast(h[q], EVOMOE_GELU_ERF);
+                            for (int q = 0; q < 8; ++q) v[q] *= sc * act_grad_fast(h[q], EVOMOE_GELU_ERF);
                         }
                         const float rv = trow < rows ? 1.f : 0.f;     // rows beyond the tile repeat its last row
 #pragma unroll
@@ -669,11 +639,10 @@ __global__ __launch_bounds__(256) void bias_grad_final_kernel(
     db1[(int64_t)g * N1 + n] = sum;
 }
 
-// Tile configurations.  BIG: one block per compute unit, 256 accumulator registers per lane.
+// Tile configurations.  BIG4: one block per compute unit, 256 accumulator registers per lane.
 // DUO: two blocks per compute unit (one's epilogue and stalls hide under the other's MFMAs).
 // LAT: for launches with no more tiles than compute units and a long contraction: what counts then is how fast
 // one block walks its K loop, and 64-wide slabs halve the number of load/barrier rounds of that walk.
-struct CfgBig { static constexpr int BM = 256, BN = 256, BK = 64, NSTAGE = 2, WPE = 1; };
 struct CfgDuo { static constexpr int BM = 128, BN = 256, BK = 32, NSTAGE = 3, WPE = 2; };
 struct CfgBig4 { static constexpr int BM = 256, BN = 256, BK = 32, NSTAGE = 4, WPE = 1; };
 struct CfgLat { static constexpr int BM = 128, BN = 256, BK = 64, NSTAGE = 3, WPE = 1; };
@@ -699,26 +668,34 @@ hipError_t launch_gemm(const Ctx& c, const GemmArgs& a, int64_t worst_tiles) {
     return launch_gemm<LAYOUT, EPI, Cfg>(c, a, worst_tiles, a, 0);
 }
 
+// Worst-case number of row tiles (launch grids and tables are sized for P_cap rows) ...
 template <class Cfg> int64_t row_tiles(const evomoe_shape& s) { return (s.P_cap + Cfg::BM - 1) / Cfg::BM + s.E; }
 template <class Cfg> int64_t ctiles(int n) { return (n + Cfg::BN - 1) / Cfg::BN; }
 template <class Cfg> int64_t mtiles(int m) { return (m + Cfg::BM - 1) / Cfg::BM; }
+// ... and the number expected: the tile shape is chosen for the pair count the caller announced
+// (evomoe_hint_pairs; the capacity when it announced none).  Any shape is correct for any pair count.
+inline int64_t expected_pairs(const Ctx& c, const evomoe_shape& s) {
+    return c.pair_hint > 0 && c.pair_hint < s.P_cap ? c.pair_hint : s.P_cap;
+}
+template <class Cfg> int64_t expected_row_tiles(const Ctx& c, const evomoe_shape& s) {
+    return (expected_pairs(c, s) + Cfg::BM - 1) / Cfg::BM + s.E / 2;
+}
 
-#ifndef EVOMOE_CFG_GEMM1
-#define EVOMOE_CFG_GEMM1 CfgBig4
-#define EVOMOE_CFG_GEMM2 CfgBig4
-#define EVOMOE_CFG_DH CfgDuo
-#define EVOMOE_CFG_DX CfgBig4
-#define EVOMOE_CFG_DW CfgBig4
-#endif
+using CfgGemm1 = CfgBig4;
+using CfgGemm2 = CfgBig4;
+using CfgDh = CfgDuo;
+using CfgDx = CfgBig4;
+using CfgDw = CfgBig4;
 
 // The 256-row tiles pay off when there are enough of them for every compute unit and the experts' row ranges
 // are long enough not to be mostly padding; otherwise the 128-row tiles (two blocks per CU) are used.
 template <class Cfg> bool prefer_small_tiles(const Ctx& c, const evomoe_shape& s, int n) {
-    return row_tiles<Cfg>(s) * ctiles<Cfg>(n) < (int64_t)c.num_cu * 3 / 2 || s.P_cap / s.E < 3 * Cfg::BM;
+    return expected_row_tiles<Cfg>(c, s) * ctiles<Cfg>(n) < (int64_t)c.num_cu * 3 / 2 ||
+           expected_pairs(c, s) / s.E < 3 * Cfg::BM;
 }
 // ... and among the 128-row configurations: LAT when (about) every tile gets a compute unit of its own
 inline bool prefer_fast_walk(const Ctx& c, const evomoe_shape& s, int n) {
-    return row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(n) <= (int64_t)c.num_cu * 5 / 4;
+    return expected_row_tiles<CfgDuo>(c, s) * ctiles<CfgDuo>(n) <= (int64_t)c.num_cu * 5 / 4;
 }
 
 }  // namespace
@@ -726,7 +703,7 @@ inline bool prefer_fast_walk(const Ctx& c, const evomoe_shape& s, int n) {
 // per-tile column sums of dH: two rows of F floats per row tile of the dH GEMM
 size_t dh_colpart_bytes(const evomoe_shape& s) {
     if (s.dtype != EVOMOE_BF16) return 0;
-    return ((size_t)row_tiles<EVOMOE_CFG_DH>(s) * 2 * s.F * sizeof(float) + 255) & ~(size_t)255;
+    return ((size_t)row_tiles<CfgDh>(s) * 2 * s.F * sizeof(float) + 255) & ~(size_t)255;
 }
 
 hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, const int32_t* pair_token,
@@ -736,7 +713,7 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
     a.expert_offsets = expert_offsets; a.E = s.E; a.P_cap = s.P_cap; a.act = s.act;
     hipError_t err;
     {   // H = X W1^T + b1, A = act(H)
-        using Cfg = EVOMOE_CFG_GEMM1;
+        using Cfg = CfgGemm1;
         ProfScope ps(c, EVOMOE_K_FFN_GEMM1);
         a.A = (const bf16_t*)x; a.lda = s.d; a.a_rows = pair_token;
         a.B = (const bf16_t*)W1; a.ldb = s.d; a.b_group_stride = (int64_t)s.F * s.d;
@@ -748,7 +725,7 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
         if (err != hipSuccess || !O) return err;      // O == nullptr: recomputation of H and A only
     }
     {   // O = A W2^T + b2
-        using Cfg = EVOMOE_CFG_GEMM2;
+        using Cfg = CfgGemm2;
         ProfScope ps(c, EVOMOE_K_FFN_GEMM2);
         a.A = (const bf16_t*)A; a.lda = s.F; a.a_rows = nullptr;
         a.B = (const bf16_t*)W2; a.ldb = s.F; a.b_group_stride = (int64_t)s.d * s.F;
@@ -765,8 +742,8 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
 
 hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, const void* H, const void* A,
                         const void* x, const int32_t* pair_token, const int32_t* expert_offsets,
-                        const void* W1, const void* W2, void* dW1, float* db1, void* dW2, float* db2,
-                        void* dXp, int accumulate, void* dH) {
+                        const void* W1, const void* W2, const void* dy, const float* pair_gate, void* dW1,
+                        float* db1, void* dW2, float* db2, void* dXp, int accumulate, void* dH) {
     GemmArgs a{};
     a.expert_offsets = expert_offsets; a.E = s.E; a.P_cap = s.P_cap; a.act = s.act;
     hipError_t err;
@@ -774,18 +751,24 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
     float* scratch = reinterpret_cast<float*>(static_cast<char*>(dH) + dh_bytes(s));
     float* colpart = reinterpret_cast<float*>(static_cast<char*>(dH) + dh_bytes(s) + colsum_scratch_bytes(s) -
                                               dh_colpart_bytes(s));
-    {   // dH = (dO W2) * act'(H); its epilogue also leaves the column sums of every tile (for db1)
-        using Cfg = EVOMOE_CFG_DH;
+    {   // dH = (dO W2) * act'(H); its epilogue also leaves the column sums of every tile (for db1).
+        // With dy and the pair weights at hand, dO W2 is taken as G_r * (dy[token(r)] W2): the rows of dy are
+        // gathered on load and the weight is applied to the f32 accumulators, so that the rounding of the stored
+        // dO (a product rounded to bf16) does not reach dH, dXp, dW1 and db1.
+        using Cfg = CfgDh;
         ProfScope ps(c, EVOMOE_K_FFN_BWD_DH);
-        a.A = (const bf16_t*)dO; a.lda = s.d; a.B = (const bf16_t*)W2; a.ldb = s.F;
+        const bool from_dy = dy && pair_gate && pair_token;
+        a.A = (const bf16_t*)(from_dy ? dy : dO); a.lda = s.d; a.a_rows = from_dy ? pair_token : nullptr;
+        a.row_scale = from_dy ? pair_gate : nullptr;
+        a.B = (const bf16_t*)W2; a.ldb = s.F;
         a.b_group_stride = (int64_t)s.d * s.F; a.N = s.F; a.K = s.d; a.Hin = (const bf16_t*)H;
         a.out1 = (bf16_t*)dH; a.colpart = db1 ? colpart : nullptr;
         err = launch_gemm<L_NN, E_ACTGRAD, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.F));
-        a.colpart = nullptr;
+        a.colpart = nullptr; a.a_rows = nullptr; a.row_scale = nullptr;
         if (err != hipSuccess) return err;
     }
     {   // dXp = dH W1
-        using Cfg = EVOMOE_CFG_DX;
+        using Cfg = CfgDx;
         ProfScope ps(c, EVOMOE_K_FFN_BWD_DX);
         a.A = (const bf16_t*)dH; a.lda = s.F; a.B = (const bf16_t*)W1; a.ldb = s.d;
         a.b_group_stride = (int64_t)s.F * s.d; a.N = s.d; a.K = s.F; a.Hin = nullptr;
@@ -799,7 +782,7 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
         if (err != hipSuccess) return err;
     }
     a.accumulate = accumulate;
-    using CfgW = EVOMOE_CFG_DW;
+    using CfgW = CfgDw;
     GemmArgs w2 = a, w1 = a;
     // dW2_g = dO_g^T A_g   [d,F]
     w2.A = (const bf16_t*)dO; w2.lda = s.d; w2.B = (const bf16_t*)A; w2.ldb = s.F;
@@ -837,7 +820,7 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
         const size_t n2 = db2 ? (size_t)s.E * s.d : 0;
         const int gx1 = db1 ? (s.F + 255) / 256 : 0, gx2 = (int)((n2 + 255) / 256);
         hipLaunchKernelGGL(bias_grad_final_kernel, dim3(s.E * gx1 + gx2), dim3(256), 0, c.stream, colpart,
-                           expert_offsets, s.E, s.P_cap, s.F, (int)EVOMOE_CFG_DH::BM, gx1, db1, scratch, n2, db2,
+                           expert_offsets, s.E, s.P_cap, s.F, (int)CfgDh::BM, gx1, db1, scratch, n2, db2,
                            accumulate);
         err = hipGetLastError();
     }

@@ -4,7 +4,8 @@
 // bf16 MFMAs against a hi/mid/lo split of W_g for a bf16 layer: a selection decided by g' > c must not
 // move), + bias + Gumbel noise, temperature softmax,
 // strict threshold with the arg-max fallback, bit mask, per-token k, and the per-expert histogram
-// (per-block partial counts, added up by gate_counts_kernel).
+// (integer atomics into counts[E] and, if asked for, into the per-256-token histograms the dispatch
+// starts from; both are cleared by gate_prep_kernel right before).
 #include <type_traits>
 
 #include "kernels.h"
@@ -18,15 +19,15 @@ namespace evomoe {
 // element r of lane (q = lane/16, i16 = lane%16) is token row 4q+r, expert column 16n+i16).
 // Adds the four waves' tiles in wave order (fixed order => reproducible bits), then 16/RT threads per
 // token apply bias, noise, temperature softmax, the strict threshold and the arg-max fallback, write
-// g', weights, mask and k, and build the per-expert histogram (per-block partials, summed afterwards by
-// gate_counts_kernel).
+// g', weights, mask and k, and add the block's per-expert counts to counts[E] and to the histogram row of the
+// 256-token group the block lies in (integer atomics: the sums do not depend on their order).
 template <int NE, int RT>
 __device__ __forceinline__ void gate_finish(
     f32x4 (&acc)[RT][NE], const float* __restrict__ bg, const float* __restrict__ noise, float tau, float c,
     int T, int E, float* __restrict__ gprime, float* __restrict__ gate_w, uint64_t* __restrict__ mask_bits,
-    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts)
+    int32_t* __restrict__ k_per_token, int32_t* __restrict__ counts, int32_t* __restrict__ block_hist)
 {
-    constexpr int TPB = 16 * RT;           // tokens per block
+    constexpr int TPB = 16 * RT;           // tokens per block (divides kDispatchTokens)
     constexpr int EP = 16 * NE;            // experts padded to MFMA tiles
     constexpr int LDZ = EP + 4;            // LDS row stride (bank-conflict-free tile writes)
     constexpr int TPT = 256 / TPB;         // threads per token in the softmax phase
@@ -106,6 +107,7 @@ __device__ __forceinline__ void gate_finish(
         const int oe = __shfl_xor(best_e, o, 64);
         if (ob > best || (ob == best && oe < best_e)) { best = ob; best_e = oe; }
     }
+    if (best_e > 63) best_e = 0;                        // no comparable score at all (a row of NaNs): expert 0
     if (tok_ok && bits == 0) bits = 1ull << best_e;     // Algorithm 2: len(id_s) >= 1
 
     if (tok_ok) {
@@ -126,38 +128,11 @@ __device__ __forceinline__ void gate_finish(
     }
     __syncthreads();
 
-    // ---- per-expert histogram: per-block partials; gate_counts_kernel adds them up afterwards ----
-    // (a last-block-done ticket would cost one device-scope atomic per block on a single address, which
-    //  at hundreds of blocks takes longer than the whole rest of the kernel)
-    if (tid < E) block_counts[(size_t)blockIdx.x * E + tid] = cnt[tid];
-}
-
-// counts[e] = sum over gate blocks of block_counts[b][e]   (one block of 1024 threads; integer, order-independent)
-__global__ __launch_bounds__(1024) void gate_counts_kernel(const int32_t* __restrict__ block_counts,
-                                                           int nblk, int E, int32_t* __restrict__ counts)
-{
-    __shared__ int cnt[64];
-    const int tid = threadIdx.x;
-    if (tid < 64) cnt[tid] = 0;
-    __syncthreads();
-    // thread -> (column e = tid % EW, row lane tid / EW): private sums first, one LDS atomic per thread
-    const int EW = E <= 16 ? 16 : (E <= 32 ? 32 : 64);
-    const int e = tid % EW, rl = tid / EW, nrl = 1024 / EW;
-    int sum = 0;
-    if (e < E)
-        for (int b0 = rl; b0 < nblk; b0 += nrl * 8) {
-            int v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int b = b0 + u * nrl;
-                v[u] = b < nblk ? block_counts[(size_t)b * E + e] : 0;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) sum += v[u];
-        }
-    if (e < E && sum) atomicAdd(&cnt[e], sum);
-    __syncthreads();
-    if (tid < E) counts[tid] = cnt[tid];
+    // ---- per-expert histogram ----
+    if (tid < E && cnt[tid]) {
+        atomicAdd(&counts[tid], cnt[tid]);
+        if (block_hist) atomicAdd(&block_hist[(size_t)(t0 / kDispatchTokens) * E + tid], cnt[tid]);
+    }
 }
 
 // float32 layer: logits with v_mfma_f32_16x16x4_f32 (exact float32 products).  Block = 4 waves; the
@@ -167,7 +142,7 @@ __global__ __launch_bounds__(256) void dts_gate_kernel(
     const TX* __restrict__ x, const float* __restrict__ Wg, const float* __restrict__ bg,
     const float* __restrict__ noise, float tau, float c, int T, int d, int E,
     float* __restrict__ gprime, float* __restrict__ gate_w, uint64_t* __restrict__ mask_bits,
-    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts)
+    int32_t* __restrict__ k_per_token, int32_t* __restrict__ counts, int32_t* __restrict__ block_hist)
 {
     constexpr int KV = Elem<TX>::kVec;     // k's per 16-byte load
     constexpr int KB = 4 * KV;             // k's per slab (4 lane groups x KV)
@@ -208,19 +183,23 @@ __global__ __launch_bounds__(256) void dts_gate_kernel(
             }
         }
     }
-    gate_finish<NE, RT>(acc, bg, noise, tau, c, T, E, gprime, gate_w, mask_bits, k_per_token, block_counts);
+    gate_finish<NE, RT>(acc, bg, noise, tau, c, T, E, gprime, gate_w, mask_bits, k_per_token, counts, block_hist);
 }
 
 // bf16 layer.  x is exact in bf16, so W_g is split into three bf16 terms (hi + mid + lo carry all 24
 // mantissa bits of the float32 weight) and the logits come from three v_mfma_f32_16x16x32_bf16 per 32 k's:
 // every product is exact in float32 and the sum is accumulated in float32 -- the same accuracy as float32
 // FMAs, at matrix-core rate, which keeps the kernel HBM-bound up to E = 64.  The split, transposed copy of
-// W_g ([3][16*NE][d] bf16, zero rows beyond E) is made by split_wg_kernel right before.
-__global__ __launch_bounds__(256) void split_wg_kernel(const float* __restrict__ Wg, int d, int E, int EP,
-                                                       uint16_t* __restrict__ planes)
+// W_g ([3][16*NE][d] bf16, zero rows beyond E) is made by gate_prep_kernel right before, which also clears the
+// integer sums the gate adds to (planes == null, float32 layer: clears only).
+__global__ __launch_bounds__(256) void gate_prep_kernel(const float* __restrict__ Wg, int d, int E, int EP,
+                                                        uint16_t* __restrict__ planes, int32_t* __restrict__ counts,
+                                                        int32_t* __restrict__ block_hist, int n_hist)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;          // over EP * d, k fastest
-    if (i >= EP * d) return;
+    if (i < E) counts[i] = 0;
+    if (block_hist && i < n_hist) block_hist[i] = 0;
+    if (!planes || i >= EP * d) return;
     const int e = i / d, k = i % d;
     const float w = e < E ? Wg[(size_t)k * E + e] : 0.f;
     const uint32_t hi = f32_to_bf16_bits(w);
@@ -239,7 +218,7 @@ __global__ __launch_bounds__(256) void dts_gate_bf16_kernel(
     const bf16_t* __restrict__ x, const bf16_t* __restrict__ planes, const float* __restrict__ bg,
     const float* __restrict__ noise, float tau, float c, int T, int d, int E,
     float* __restrict__ gprime, float* __restrict__ gate_w, uint64_t* __restrict__ mask_bits,
-    int32_t* __restrict__ k_per_token, int32_t* __restrict__ block_counts)
+    int32_t* __restrict__ k_per_token, int32_t* __restrict__ counts, int32_t* __restrict__ block_hist)
 {
     constexpr int TPB = 16 * RT, EP = 16 * NE;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -295,228 +274,7 @@ __global__ __launch_bounds__(256) void dts_gate_bf16_kernel(
                 }
         }
     }
-    gate_finish<NE, RT>(acc, bg, noise, tau, c, T, E, gprime, gate_w, mask_bits, k_per_token, block_counts);
-}
-
-// bf16 layer, E <= 32, and the three bf16 terms of W_g fit the LDS next to nothing else: a streaming form of the
-// same computation.  One block of 16 waves per compute unit builds the terms in LDS once ([term][expert][k], rows
-// padded by 16 bytes so that the sixteen experts of a fragment read land in different banks), then every wave
-// works through 16-token tiles on its own -- no K split, no block barrier: x fragments are fetched a group of
-// eight k-blocks ahead (two register buffers, the next tile's first group under the current tile's last), the
-// softmax over the experts is a butterfly over the 16 lanes that share a token, and the expert counts stay in
-// registers until the block ends.
-template <int NE>
-__global__ __launch_bounds__(1024) void dts_gate_stream_kernel(
-    const bf16_t* __restrict__ x, const float* __restrict__ Wg, const float* __restrict__ bg,
-    const float* __restrict__ noise, float tau, float c, int T, int d, int E, float* __restrict__ gprime,
-    float* __restrict__ gate_w, uint64_t* __restrict__ mask_bits, int32_t* __restrict__ k_per_token,
-    int32_t* __restrict__ block_counts)
-{
-    constexpr int EP = 16 * NE;
-    constexpr int G = 8;                              // k-blocks (of 32) per register buffer
-    extern __shared__ __align__(16) unsigned char gsm[];
-    __shared__ int cnt[32];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int i16 = lane & 15, q = lane >> 4;
-    const int row_bytes = d * 2 + 16;                 // one expert's k range of one term
-    const int plane_bytes = EP * row_bytes;
-
-    // ---- W_g -> three bf16 terms in LDS (hi + mid + lo carry all 24 mantissa bits) ----
-    if (tid < 32) cnt[tid] = 0;
-    for (int i0 = tid; i0 < EP * d; i0 += 8 * 1024) {        // eight loads in flight per thread
-        float w[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int i = i0 + u * 1024, e = i % EP, k = i / EP;    // consecutive threads: consecutive experts of one k
-            w[u] = (i < EP * d && e < E) ? Wg[(size_t)k * E + e] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int i = i0 + u * 1024, e = i % EP, k = i / EP;
-            if (i < EP * d) {
-                const bf16_t h = (bf16_t)w[u];
-                const float r1 = w[u] - (float)h;
-                const bf16_t m = (bf16_t)r1;
-                const bf16_t l = (bf16_t)(r1 - (float)m);
-                unsigned char* at = gsm + e * row_bytes + k * 2;
-                *reinterpret_cast<bf16_t*>(at) = h;
-                *reinterpret_cast<bf16_t*>(at + plane_bytes) = m;
-                *reinterpret_cast<bf16_t*>(at + 2 * plane_bytes) = l;
-            }
-        }
-    }
-    __syncthreads();
-
-    const int nkb = (d + 31) / 32;                    // d is a multiple of 8: the last k-block may be partial
-    const int ngr = (nkb + G - 1) / G;                // groups per tile
-    const int ntiles = (T + 15) / 16;
-    const int nw = gridDim.x * 16;                    // waves in the grid
-    // tiles first, first + nw, ...: the sixteen waves of a block take sixteen consecutive tiles (one contiguous
-    // 16 x 16 x d stretch of x at a time)
-    const int first = blockIdx.x * 16 + wave;
-    const int my_tiles = first < ntiles ? (ntiles - first + nw - 1) / nw : 0;
-    const int nsteps = my_tiles * ngr;
-
-    float bgv[NE];
-#pragma unroll
-    for (int n = 0; n < NE; ++n) bgv[n] = (bg && n * 16 + i16 < E) ? bg[n * 16 + i16] : 0.f;
-    int mycnt[NE];
-#pragma unroll
-    for (int n = 0; n < NE; ++n) mycnt[n] = 0;
-
-    const bf16x8 zero8 = {};
-    bf16x8 xa[2][G];
-    float nz[2][NE][4];                               // noise of this wave's even / odd tiles
-    auto fetch_noise = [&](int tile, float (&nbuf)[NE][4]) {
-#pragma unroll
-        for (int n = 0; n < NE; ++n)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int tt = tile * 16 + 4 * q + r, e = n * 16 + i16;
-                nbuf[n][r] = (noise && tt < T && e < E) ? noise[(size_t)tt * E + e] : 0.f;
-            }
-    };
-    // step s = (tile number s / ngr of this wave, group s % ngr): loads of its x fragments (and, with a tile's
-    // first group, of the tile's noise)
-    auto fetch = [&](int s, bf16x8 (&buf)[G]) {
-        const int j = s / ngr;
-        const int tile = first + j * nw, g = s % ngr;
-        const int t = min(tile * 16 + i16, T - 1);
-#pragma unroll
-        for (int u = 0; u < G; ++u) {
-            const int k0 = (g * G + u) * 32 + q * 8;
-            buf[u] = k0 < d ? *reinterpret_cast<const bf16x8*>(x + (size_t)t * d + k0) : zero8;
-        }
-        if (g == 0) {
-            if (j & 1) fetch_noise(tile, nz[1]);
-            else fetch_noise(tile, nz[0]);
-        }
-    };
-    f32x4 acc[NE];
-    auto finish = [&](int tile, float (&nbuf)[NE][4]) {
-        // the tile's logits are complete: element r of lane (q, i16) is token 4q + r, expert 16n + i16
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int t = tile * 16 + 4 * q + r;
-            const bool tok_ok = t < T;
-            float a[NE];
-            float m = -INFINITY;
-#pragma unroll
-            for (int n = 0; n < NE; ++n) {
-                const int e = n * 16 + i16;
-                a[n] = e < E ? (acc[n][r] + bgv[n] + nbuf[n][r]) / tau : -INFINITY;
-                m = fmaxf(m, a[n]);
-            }
-#pragma unroll
-            for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 16));
-            float ssum = 0.f;
-#pragma unroll
-            for (int n = 0; n < NE; ++n) {
-                a[n] = (n * 16 + i16 < E) ? expf(a[n] - m) : 0.f;
-                ssum += a[n];
-            }
-#pragma unroll
-            for (int o = 8; o > 0; o >>= 1) ssum += __shfl_xor(ssum, o, 16);
-            uint32_t bits = 0;
-            float best = -1.f;
-            int best_e = 0x7fffffff;
-#pragma unroll
-            for (int n = 0; n < NE; ++n) {
-                const int e = n * 16 + i16;
-                a[n] = a[n] / ssum;
-                if (e < E) {
-                    if (a[n] > c) bits |= 1u << e;
-                    if (a[n] > best) { best = a[n]; best_e = e; }      // ascending e: lowest index on ties
-                }
-            }
-#pragma unroll
-            for (int o = 8; o > 0; o >>= 1) {
-                bits |= __shfl_xor(bits, o, 16);
-                const float ob = __shfl_xor(best, o, 16);
-                const int oe = __shfl_xor(best_e, o, 16);
-                if (ob > best || (ob == best && oe < best_e)) { best = ob; best_e = oe; }
-            }
-            if (bits == 0) bits = 1u << best_e;       // Algorithm 2: len(id_s) >= 1
-            if (tok_ok) {
-#pragma unroll
-                for (int n = 0; n < NE; ++n) {
-                    const int e = n * 16 + i16;
-                    if (e < E) {
-                        const bool sel = (bits >> e) & 1u;
-                        gprime[(size_t)t * E + e] = a[n];
-                        if (gate_w) gate_w[(size_t)t * E + e] = sel ? a[n] : 0.f;
-                        mycnt[n] += sel ? 1 : 0;
-                    }
-                }
-                if (i16 == 0) {
-                    mask_bits[t] = (uint64_t)bits;
-                    if (k_per_token) k_per_token[t] = __popc(bits);
-                }
-            }
-        }
-    };
-    auto work = [&](int s, bf16x8 (&buf)[G]) {
-        const int j = s / ngr;
-        const int tile = first + j * nw, g = s % ngr;
-        if (g == 0) {
-#pragma unroll
-            for (int n = 0; n < NE; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-#pragma unroll
-        for (int u = 0; u < G; ++u) {
-            const int k0 = (g * G + u) * 32 + q * 8;
-            if ((g * G + u) * 32 < d) {               // wave-uniform
-                const int kc = min(k0, d - 8);        // lanes beyond d in a partial k-block: their x fragment is zero
-#pragma unroll
-                for (int n = 0; n < NE; ++n) {
-                    const unsigned char* at = gsm + (n * 16 + i16) * row_bytes + kc * 2;
-                    const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(at);
-                    const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(at + plane_bytes);
-                    const bf16x8 b2 = *reinterpret_cast<const bf16x8*>(at + 2 * plane_bytes);
-                    acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[u], b2, acc[n], 0, 0, 0);
-                    acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[u], b1, acc[n], 0, 0, 0);
-                    acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[u], b0, acc[n], 0, 0, 0);
-                }
-            }
-        }
-        if (g != ngr - 1) return;
-        if (j & 1) finish(tile, nz[1]);
-        else finish(tile, nz[0]);
-    };
-    if (nsteps > 0) fetch(0, xa[0]);
-    for (int s = 0; s < nsteps; s += 2) {
-        if (s + 1 < nsteps) fetch(s + 1, xa[1]);
-        work(s, xa[0]);
-        if (s + 2 < nsteps) fetch(s + 2, xa[0]);
-        if (s + 1 < nsteps) work(s + 1, xa[1]);
-    }
-    // ---- expert counts: the four lane groups of a wave hold different tokens of the same experts ----
-#pragma unroll
-    for (int n = 0; n < NE; ++n) {
-        int v = mycnt[n];
-        v += __shfl_xor(v, 16, 64);
-        v += __shfl_xor(v, 32, 64);
-        if (q == 0 && v) atomicAdd(&cnt[n * 16 + i16], v);
-    }
-    __syncthreads();
-    if (tid < E) block_counts[(size_t)blockIdx.x * E + tid] = cnt[tid];
-}
-
-// the streaming kernel's LDS need; it is used when this fits (and E <= 32)
-static size_t gate_stream_lds(const evomoe_shape& s) {
-    const size_t ep = s.E <= 16 ? 16 : 32;
-    return 3 * ep * ((size_t)s.d * 2 + 16);
-}
-static int gate_stream_grid(const Ctx& c, const evomoe_shape& s) {
-    const int ntiles = (s.T + 15) / 16;
-    return ntiles < c.num_cu ? ntiles : c.num_cu;
-}
-// ... and there is at least one 16-token tile for every wave of the grid (65536 tokens on 256 CUs): with fewer,
-// most waves would idle and a tile's K range would be walked by one wave alone, which the tiled kernel (K split
-// over a block's four waves) does in half the time
-static bool gate_use_stream(const Ctx& c, const evomoe_shape& s) {
-    return s.dtype == EVOMOE_BF16 && s.E <= 32 && gate_stream_lds(s) <= 150 * 1024 &&
-           (s.T + 15) / 16 >= 16 * c.num_cu;
+    gate_finish<NE, RT>(acc, bg, noise, tau, c, T, E, gprime, gate_w, mask_bits, k_per_token, counts, block_hist);
 }
 
 static int pick_rt(const Ctx& c, const evomoe_shape& s) {
@@ -527,89 +285,67 @@ static int pick_rt(const Ctx& c, const evomoe_shape& s) {
     return 1;
 }
 
-int gate_blocks(const Ctx& c, const evomoe_shape& s) {
-    if (gate_use_stream(c, s)) return gate_stream_grid(c, s);
-    const int tpb = 16 * pick_rt(c, s);
-    return (s.T + tpb - 1) / tpb;
-}
 
 template <typename TX, int NE, int RT>
 static hipError_t gate_launch_t(const Ctx& c, const evomoe_shape& s, const void* x, const float* Wg,
                                 const float* bg, const float* noise, float tau, float thr,
                                 float* gprime, float* gate_w, uint64_t* mask_bits, int32_t* counts,
-                                int32_t* k_per_token) {
+                                int32_t* k_per_token, int32_t* block_hist) {
     const int blocks = (s.T + 16 * RT - 1) / (16 * RT);
+    const int n_hist = dispatch_blocks(s) * s.E;
     ProfScope ps(c, EVOMOE_K_GATE);
     if constexpr (std::is_same<TX, bf16_t>::value) {
         const int ep = 16 * NE;
-        hipLaunchKernelGGL(split_wg_kernel, dim3((ep * s.d + 255) / 256), dim3(256), 0, c.stream, Wg, s.d,
-                           s.E, ep, c.wg_planes);
+        const int n = ep * s.d > n_hist ? ep * s.d : n_hist;
+        hipLaunchKernelGGL(gate_prep_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, Wg, s.d, s.E, ep,
+                           c.wg_planes, counts, block_hist, n_hist);
         hipLaunchKernelGGL((dts_gate_bf16_kernel<NE, RT>), dim3(blocks), dim3(256), 0, c.stream,
                            (const bf16_t*)x, (const bf16_t*)c.wg_planes, bg, noise, tau, thr, s.T, s.d, s.E,
-                           gprime, gate_w, mask_bits, k_per_token, c.block_counts);
+                           gprime, gate_w, mask_bits, k_per_token, counts, block_hist);
     } else {
+        const int n = n_hist > s.E ? n_hist : s.E;
+        hipLaunchKernelGGL(gate_prep_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, Wg, s.d, s.E, 0,
+                           (uint16_t*)nullptr, counts, block_hist, n_hist);
         hipLaunchKernelGGL((dts_gate_kernel<TX, NE, RT>), dim3(blocks), dim3(256), 0, c.stream,
                            (const TX*)x, Wg, bg, noise, tau, thr, s.T, s.d, s.E, gprime, gate_w,
-                           mask_bits, k_per_token, c.block_counts);
+                           mask_bits, k_per_token, counts, block_hist);
     }
-    hipLaunchKernelGGL(gate_counts_kernel, dim3(1), dim3(1024), 0, c.stream, c.block_counts, blocks, s.E, counts);
     return hipGetLastError();
 }
 
 template <typename TX, int NE>
 static hipError_t gate_launch_rt(int rt, const Ctx& c, const evomoe_shape& s, const void* x,
                                  const float* Wg, const float* bg, const float* noise, float tau,
-                                 float thr, float* gp, float* gw, uint64_t* mb, int32_t* cn, int32_t* kt) {
+                                 float thr, float* gp, float* gw, uint64_t* mb, int32_t* cn, int32_t* kt, int32_t* bh) {
     switch (rt) {
-        case 4: return gate_launch_t<TX, NE, 4>(c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
-        case 2: return gate_launch_t<TX, NE, 2>(c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
-        default: return gate_launch_t<TX, NE, 1>(c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
+        case 4: return gate_launch_t<TX, NE, 4>(c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt, bh);
+        case 2: return gate_launch_t<TX, NE, 2>(c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt, bh);
+        default: return gate_launch_t<TX, NE, 1>(c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt, bh);
     }
 }
 
 template <typename TX>
 static hipError_t gate_launch_ne(const Ctx& c, const evomoe_shape& s, const void* x, const float* Wg,
                                  const float* bg, const float* noise, float tau, float thr, float* gp,
-                                 float* gw, uint64_t* mb, int32_t* cn, int32_t* kt) {
+                                 float* gw, uint64_t* mb, int32_t* cn, int32_t* kt, int32_t* bh) {
     const int rt = pick_rt(c, s);
     switch ((s.E + 15) / 16) {
-        case 1: return gate_launch_rt<TX, 1>(rt, c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
-        case 2: return gate_launch_rt<TX, 2>(rt, c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
-        case 3: return gate_launch_rt<TX, 3>(rt, c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
-        default: return gate_launch_rt<TX, 4>(rt, c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt);
+        case 1: return gate_launch_rt<TX, 1>(rt, c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt, bh);
+        case 2: return gate_launch_rt<TX, 2>(rt, c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt, bh);
+        case 3: return gate_launch_rt<TX, 3>(rt, c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt, bh);
+        default: return gate_launch_rt<TX, 4>(rt, c, s, x, Wg, bg, noise, tau, thr, gp, gw, mb, cn, kt, bh);
     }
 }
 
 hipError_t launch_dts_gate(const Ctx& c, const evomoe_shape& s, const void* x, const float* Wg,
                            const float* bg, const float* noise, float tau, float threshold,
                            float* gprime, float* gate_w, uint64_t* mask_bits, int32_t* counts,
-                           int32_t* k_per_token) {
-    if (gate_use_stream(c, s)) {
-        const int grid = gate_stream_grid(c, s);
-        const size_t lds = gate_stream_lds(s);
-        ProfScope ps(c, EVOMOE_K_GATE);
-        auto go = [&](auto kern) -> hipError_t {
-            static bool configured = false;           // (one flag per instantiation of this lambda's call operator)
-            if (!configured) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
-                if (e != hipSuccess) return e;
-                configured = true;
-            }
-            hipLaunchKernelGGL(kern, dim3(grid), dim3(1024), lds, c.stream, (const bf16_t*)x, Wg, bg, noise, tau,
-                               threshold, s.T, s.d, s.E, gprime, gate_w, mask_bits, k_per_token, c.block_counts);
-            return hipGetLastError();
-        };
-        hipError_t err = s.E <= 16 ? go(dts_gate_stream_kernel<1>) : go(dts_gate_stream_kernel<2>);
-        if (err != hipSuccess) return err;
-        hipLaunchKernelGGL(gate_counts_kernel, dim3(1), dim3(1024), 0, c.stream, c.block_counts, grid, s.E, counts);
-        return hipGetLastError();
-    }
+                           int32_t* k_per_token, int32_t* block_hist) {
     if (s.dtype == EVOMOE_BF16)
         return gate_launch_ne<bf16_t>(c, s, x, Wg, bg, noise, tau, threshold, gprime, gate_w,
-                                      mask_bits, counts, k_per_token);
+                                      mask_bits, counts, k_per_token, block_hist);
     return gate_launch_ne<float>(c, s, x, Wg, bg, noise, tau, threshold, gprime, gate_w, mask_bits,
-                                 counts, k_per_token);
+                                 counts, k_per_token, block_hist);
 }
 
 // ---------------------------------------------------------------------------------------------

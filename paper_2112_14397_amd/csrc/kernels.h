@@ -8,8 +8,7 @@ namespace evomoe {
 hipError_t launch_dts_gate(const Ctx& c, const evomoe_shape& s, const void* x, const float* Wg,
                            const float* bg, const float* noise, float tau, float threshold,
                            float* gprime, float* gate_w, uint64_t* mask_bits, int32_t* counts,
-                           int32_t* k_per_token);
-int gate_blocks(const Ctx& c, const evomoe_shape& s);   // grid size of the gate kernel (scratch rows)
+                           int32_t* k_per_token, int32_t* block_hist);
 hipError_t launch_dts_gate_bwd(const Ctx& c, const evomoe_shape& s, const float* dG_pairs,
                                const int32_t* tok_off, const int32_t* tok_rows, const float* gprime,
                                const uint64_t* mask_bits, float tau, const void* x, const float* Wg,
@@ -23,14 +22,19 @@ hipError_t launch_balance_loss(const Ctx& c, const evomoe_shape& s, const float*
 
 // dispatch.hip
 hipError_t launch_dispatch(const Ctx& c, const evomoe_shape& s, const uint64_t* mask_bits,
-                           const float* scores, int32_t* expert_offsets, int32_t* pair_token,
-                           float* pair_gate, int32_t* tok_off, int32_t* tok_rows, int64_t* num_pairs,
-                           const void* x, void* x_perm);
-int dispatch_blocks(const evomoe_shape& s);
+                           const float* scores, const int32_t* block_hist, int32_t* expert_offsets,
+                           int32_t* pair_token, float* pair_gate, int32_t* tok_off, int32_t* tok_rows,
+                           int64_t* num_pairs, const void* x, void* x_perm);
+int dispatch_blocks(const evomoe_shape& s);     // 256-token groups: rows of a block_hist table
 hipError_t launch_gather_rows(const Ctx& c, const evomoe_shape& s, const void* x, const int32_t* pair_token,
                               const int32_t* expert_offsets, void* x_perm);   // x_perm[r,:] = x[pair_token[r],:]
 hipError_t launch_dispatch_bwd(const Ctx& c, const evomoe_shape& s, const void* dXp,
                                const int32_t* tok_off, const int32_t* tok_rows, void* dx);
+
+// diversify.hip
+hipError_t launch_diversify(const Ctx& c, const evomoe_shape& s, const void* W1s, const float* b1s, const void* W2s,
+                            const float* b2s, uint64_t seed, float mask_ratio, void* W1, float* b1, void* W2,
+                            float* b2);
 
 // combine.hip
 hipError_t launch_combine(const Ctx& c, const evomoe_shape& s, const void* O, const float* pair_gate,
@@ -46,13 +50,15 @@ hipError_t launch_expert_ffn(const Ctx& c, const evomoe_shape& s, const void* x,
 hipError_t launch_expert_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, const void* H,
                                  const void* A, const void* x, const int32_t* pair_token,
                                  const int32_t* expert_offsets, const void* W1, const void* W2,
+                                 const void* dy, const float* pair_gate,
                                  void* dW1, float* db1, void* dW2, float* db2, void* dXp,
                                  int accumulate, void* workspace);
 size_t ffn_bwd_workspace_bytes(const evomoe_shape& s);
 size_t ffn_bwd_recompute_workspace_bytes(const evomoe_shape& s);
 hipError_t launch_expert_ffn_bwd_recompute(const Ctx& c, const evomoe_shape& s, const void* dO, const void* x,
                                            const int32_t* pair_token, const int32_t* expert_offsets,
-                                           const void* W1, const float* b1, const void* W2, void* dW1,
+                                           const void* W1, const float* b1, const void* W2, const void* dy,
+                                           const float* pair_gate, void* dW1,
                                            float* db1, void* dW2, float* db2, void* dXp, int accumulate,
                                            void* workspace);
 

@@ -1,7 +1,7 @@
 """Condense rocprofv3 output into the short text summaries kept under profiles/.
 
-    python -m paper_2112_14397_amd.profile_summary stats  <dir with *_kernel_stats.csv>
-    python -m paper_2112_14397_amd.profile_summary pmc    <dir with *_counter_collection.csv> [--copy-bytes N]
+    python profile_summary.py stats  <dir with *_kernel_stats.csv>
+    python profile_summary.py pmc    <dir with *_counter_collection.csv> [--copy-bytes N]
 
 `stats` prints per-kernel calls / total / average duration.  `pmc` prints, per kernel, the average of every
 collected counter per dispatch; with --copy-bytes it also derives the scale factor of FETCH_SIZE / WRITE_SIZE

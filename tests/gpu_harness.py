@@ -5,20 +5,20 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from helpers import tol_ok
+from helpers import tol_ok, tol_stats
 from oracle import evomoe_oracle as orc
 from paper_2112_14397_amd import binding as B
-from paper_2112_14397_amd import synth
+import synth_inputs as synth
 
 RTOL = {"f32": 1e-5, "bf16": 2e-2}
-# Outputs of a bf16 layer that sit behind two or more bf16-stored intermediates joined by contractions that
-# nearly cancel (dO -> dH -> dXp, dW1, db1;  O -> dG -> dx, dW_g, db_g).  Each stored value carries 2^-9
-# relative rounding; a contraction whose terms cancel 100-fold turns that into percents of a single result,
-# and over ~10^7 elements the 4-5 sigma tail of the end-to-end error reaches 1.3x the plain bound (emulating
-# the storage roundings on the CPU reproduces the kernels' values to 0.5x).  Whole-layer comparisons at that
-# scale hold these outputs to CHAIN_SLACK x the tolerance end to end (and dx, dW_g, db_g to 1x per stage).
-CHAIN_OUTPUTS = ("dXp", "dW1", "db1", "dx", "dWg", "dbg")
-CHAIN_SLACK = {name: 2.0 for name in CHAIN_OUTPUTS}
+# Every output of a bf16 layer is held to the plain tolerance end to end, with one measured exception, for
+# whole-layer comparisons of millions of elements only: dx.  Its gate share, W_g dz with dz ~ (g'/tau) dG and
+# dG = <dy, O>, carries the bf16 rounding of the stored activations A (which the matrix cores consume as bf16,
+# so it cannot be avoided) and of O, multiplied by 1/tau; rounding those two values alone in the float64 oracle
+# puts the worst of config 2's 6.3 million dx elements at 1.2x the bound at tau = 0.3.  DX_TAIL bounds that tail:
+# no element above DX_TAIL[0] x the bound and at most DX_TAIL[1] elements above 1x; per stage (the oracle's last
+# stages fed with the dG and dXp the kernels produced) dx is held to 1x like everything else.
+DX_TAIL = (1.35, 32)
 BAND = 1e-6     # pairs with |g' - c| below this are excluded from the mask comparison (and counted)
 
 
@@ -135,12 +135,14 @@ def compare_forward(gl: GpuLayer, inp: synth.LayerInputs, tau, c, report=None, c
     return fwd, P, n_band, n_flip
 
 
-def compare_backward(gl: GpuLayer, inp: synth.LayerInputs, fwd: orc.LayerFwd, tau, slack=None, balance_alpha=None):
-    """`slack` maps an output's name to a factor on its tolerance (end-to-end comparison of outputs
-    that sit behind several bf16-stored intermediates; see compare_backward_stages)."""
+def compare_backward(gl: GpuLayer, inp: synth.LayerInputs, fwd: orc.LayerFwd, tau, dx_tail=None, balance_alpha=None,
+                     stats=None):
+    """Every backward output against the oracle at the plain tolerance.  dx_tail = (factor, count), whole
+    full-size layers only: dx may have up to `count` elements above the bound, none above factor x the bound.
+    stats (a dict), if given, receives per output (worst, elements above 1x) for the per-row and the per-tensor
+    form of the bound."""
     cfg = inp.cfg
     rt = RTOL[cfg.dtype]
-    slack = slack or {}
     gl.backward(tau, balance_alpha=balance_alpha)
     b = gl.buf
     P = int(fwd.disp.expert_offsets[cfg.E])
@@ -163,32 +165,59 @@ def compare_backward(gl: GpuLayer, inp: synth.LayerInputs, fwd: orc.LayerFwd, ta
               ("dWg", np_of(b.dWg), ref.dWg), ("dbg", np_of(b.dbg), ref.dbg), ("dx", np_of(b.dx), ref.dx))
     worsts = {}
     for name, got, want in checks:
-        ok, worst = tol_ok(got, want, rt * slack.get(name, 1.0))
+        worst, above = tol_stats(got, want, rt)
         worsts[name] = worst
-        assert ok, f"{name}: worst err/bound {worst:.3g} (rtol {rt * slack.get(name, 1.0)})"
+        if stats is not None:
+            stats[name] = {"row": (round(worst, 3), above), "tensor": tuple(
+                round(v, 3) if isinstance(v, float) else v for v in tol_stats(got, want, rt, per_tensor=True))}
+        if name == "dx" and dx_tail is not None:
+            assert worst <= dx_tail[0] and above <= dx_tail[1], \
+                f"dx: worst err/bound {worst:.3g}, {above} elements above the bound (allowed {dx_tail})"
+        else:
+            assert above == 0, f"{name}: worst err/bound {worst:.3g}, {above} elements above it (rtol {rt})"
     return ref, worsts
 
 
 def compare_backward_stages(gl: GpuLayer, inp: synth.LayerInputs, fwd: orc.LayerFwd, tau):
-    """The last two backward stages on their own: the oracle's dispatch and gate backward fed with the dG
-    and dXp the kernels produced (both compared with the oracle in compare_backward), against the kernels'
-    dx, dWg, dbg at the plain tolerance.  dG = <dy, O> nearly cancels for some pairs, so the bf16 rounding
-    of the stored O shows up in it amplified; this check separates that inherited error from the stages'."""
+    """Every backward stage on its own, at the plain tolerance: the oracle's stage fed with what the kernels'
+    stage consumed (the stored H, O, dO, dG, dXp, widened to float64) against what the kernels' stage
+    produced.  This separates a stage's own error from what it inherits through bf16-stored intermediates."""
     cfg = inp.cfg
     rt = RTOL[cfg.dtype]
     b = gl.buf
     dp = fwd.disp
     P = int(dp.expert_offsets[cfg.E])
-    dGg = np_of(b.dG_pairs)[:P].astype(np.float64)
-    dXpg = np_of(b.dXp)[:P].astype(np.float64)
-    _, dWg, dbg, dx_g = orc.dts_gate_bwd(dGg, dp.pair_token, dp.pair_expert, fwd.gate.gprime, tau, inp.x, inp.Wg)
-    dx_e = orc.dispatch_bwd(dXpg, dp.tok_off, dp.tok_rows, cfg.T)
+    f64 = lambda t: np_of(t)[:P].astype(np.float64)
+    Hg, Og, dOg, dGg, dXpg = f64(b.H), f64(b.O), f64(b.dO), f64(b.dG_pairs), f64(b.dXp)
     worsts = {}
-    for name, got, want in (("dx", np_of(b.dx), dx_e + dx_g), ("dWg", np_of(b.dWg), dWg),
-                            ("dbg", np_of(b.dbg)[None, :], dbg[None, :])):
+
+    def chk(name, got, want):
         ok, worst = tol_ok(got, want, rt)
         worsts[name] = worst
         assert ok, f"{name} (stage): worst err/bound {worst:.3g} (rtol {rt})"
+
+    # combine backward from the stored O
+    dO_s, dG_s = orc.combine_bwd(inp.dy, Og, dp.pair_gate, dp.pair_token)
+    chk("dO", np_of(b.dO)[:P], dO_s)
+    chk("dG_pairs", np_of(b.dG_pairs)[:P], dG_s)
+    # expert FFN backward from the stored H: the dH chain takes dO = G dy as the kernels do (unrounded product),
+    # the dW2 / db2 sums take the stored dO
+    ffn_exact = orc.expert_ffn_bwd(dO_s, Hg, inp.x, dp.pair_token, dp.expert_offsets, inp.W1, inp.W2, cfg.act)
+    chk("dXp", np_of(b.dXp)[:P], ffn_exact.dXp)
+    chk("dW1", np_of(b.dW1), ffn_exact.dW1)
+    chk("db1", np_of(b.db1), ffn_exact.db1)
+    if cfg.dtype == "bf16":
+        ffn_stored = orc.expert_ffn_bwd(dOg, Hg, inp.x, dp.pair_token, dp.expert_offsets, inp.W1, inp.W2, cfg.act)
+    else:
+        ffn_stored = ffn_exact
+    chk("dW2", np_of(b.dW2), ffn_stored.dW2)
+    chk("db2", np_of(b.db2), ffn_stored.db2)
+    # dispatch and gate backward from the stored dXp and dG
+    _, dWg, dbg, dx_g = orc.dts_gate_bwd(dGg, dp.pair_token, dp.pair_expert, fwd.gate.gprime, tau, inp.x, inp.Wg)
+    dx_e = orc.dispatch_bwd(dXpg, dp.tok_off, dp.tok_rows, cfg.T)
+    chk("dx", np_of(b.dx), dx_e + dx_g)
+    chk("dWg", np_of(b.dWg), dWg)
+    chk("dbg", np_of(b.dbg)[None, :], dbg[None, :])
     return worsts
 
 

@@ -40,7 +40,7 @@ def test_status_strings_and_workspace_query():
 def test_null_context_is_rejected_without_a_gpu():
     L = B.lib()
     s = B.make_shape(8, 8, 2, 8, "f32", "relu", 16)
-    assert L.evomoe_dts_gate(None, ctypes.byref(s), None, None, None, None, 1.0, 0.1, None, None, None, None, None) == B.EVOMOE_EINVAL
+    assert L.evomoe_dts_gate(None, ctypes.byref(s), None, None, None, None, 1.0, 0.1, None, None, None, None, None, None) == B.EVOMOE_EINVAL
     assert L.evomoe_combine(None, ctypes.byref(s), None, None, None, None, None) == B.EVOMOE_EINVAL
     assert L.evomoe_destroy(None) == B.EVOMOE_EINVAL
     assert L.evomoe_create(None, None) == B.EVOMOE_EINVAL

@@ -6,8 +6,9 @@ import pytest
 import torch
 
 from paper_2112_14397_amd import binding as B
-from paper_2112_14397_amd import synth
+import synth_inputs as synth
 import gpu_harness as H
+from oracle import evomoe_oracle as orc
 
 pytestmark = pytest.mark.gpu
 
@@ -101,7 +102,7 @@ def test_recompute_full_size_gpt_whole_layer():
     gl = H.GpuLayer(inp, P_cap=20000, recompute=True)
     fwd, P, _, _ = H.compare_forward(gl, inp, tau, cfg.threshold)
     gl.buf.H.fill_(float("nan")); gl.buf.A.fill_(float("nan"))
-    H.compare_backward(gl, inp, fwd, tau, slack=H.CHAIN_SLACK)
+    H.compare_backward(gl, inp, fwd, tau, dx_tail=H.DX_TAIL)
 
 
 def test_argument_errors_of_the_added_entry_points():
@@ -111,8 +112,8 @@ def test_argument_errors_of_the_added_entry_points():
     gl.forward(0.7, cfg.threshold)
     with pytest.raises(B.EvoMoEError) as e:           # recompute needs its own, larger workspace
         B.evomoe_expert_ffn_bwd_recompute(gl.ctx, s, b.dO, gl.x, b.pair_token, b.expert_offsets, gl.params.W1,
-                                          gl.params.b1, gl.params.W2, b.dW1, b.db1, b.dW2, b.db2, b.dXp, False,
-                                          b.workspace)
+                                          gl.params.b1, gl.params.W2, None, None, b.dW1, b.db1, b.dW2, b.db2, b.dXp,
+                                          False, b.workspace)
     assert e.value.status == B.EVOMOE_EWORKSPACE
     with pytest.raises(B.EvoMoEError) as e:
         B.evomoe_balance_loss(gl.ctx, s, b.gprime, b.counts, 0.1, None, b.bal_coef)
@@ -143,7 +144,8 @@ def test_ffn_backward_with_some_outputs_left_out(dtype):
             getattr(b, n).fill_(float("nan"))
         arg = lambda n: getattr(b, n) if n in keep else None
         B.evomoe_expert_ffn_bwd(gl.ctx, gl.shape, b.dO, b.H, b.A, gl.x, b.pair_token, b.expert_offsets, p.W1, p.W2,
-                                arg("dW1"), arg("db1"), arg("dW2"), arg("db2"), b.dXp, False, b.workspace)
+                                gl.dy, b.pair_gate, arg("dW1"), arg("db1"), arg("dW2"), arg("db2"), b.dXp, False,
+                                b.workspace)
         torch.cuda.synchronize()
         P = B.evomoe_num_pairs(gl.ctx, b.num_pairs)
         assert torch.equal(b.dXp[:P], full["dXp"][:P]), f"dXp with {keep}"
@@ -152,3 +154,37 @@ def test_ffn_backward_with_some_outputs_left_out(dtype):
                 assert torch.equal(getattr(b, n), full[n]), f"{n} with {keep}"
             else:
                 assert torch.isnan(getattr(b, n).float()).all(), f"{n} was written although it was left out"
+
+
+# ---- expert-diversify: N experts spawned from the shared one by seeded random masks (Algorithm 1, diversify loop) ----
+
+@pytest.mark.parametrize("dtype,d,F,E,ratio", [("bf16", 768, 3072, 16, 0.25), ("f32", 72, 136, 5, 0.5),
+                                               ("bf16", 64, 64, 64, 0.0), ("bf16", 136, 264, 3, 1.0)])
+def test_diversify_masks_match_the_oracle_bit_for_bit(dtype, d, F, E, ratio):
+    rng = np.random.default_rng(77 + d)
+    W1s = synth.round_to_storage(rng.standard_normal((F, d)).astype(np.float32) * 0.02, dtype)
+    W2s = synth.round_to_storage(rng.standard_normal((d, F)).astype(np.float32) * 0.02, dtype)
+    b1s = rng.standard_normal(F).astype(np.float32)
+    b2s = rng.standard_normal(d).astype(np.float32)
+    seed = 0x9E3779B97F4A7C15 ^ (d * 1000003)          # exercises the upper 32 bits of the seed
+    ref = orc.diversify(W1s, b1s, W2s, b2s, E, seed, ratio)
+    dt = B.torch_dtype(dtype)
+    ctx = B.Context()
+    shape = B.make_shape(16, d, E, F, dtype, "gelu", 16)
+    dev = lambda a, t=None: H.to_dev(a, t)
+    W1 = torch.full((E, F, d), float("nan"), dtype=dt, device="cuda")
+    W2 = torch.full((E, d, F), float("nan"), dtype=dt, device="cuda")
+    b1 = torch.full((E, F), float("nan"), dtype=torch.float32, device="cuda")
+    b2 = torch.full((E, d), float("nan"), dtype=torch.float32, device="cuda")
+    B.evomoe_diversify(ctx, shape, dev(W1s, dt), dev(b1s), dev(W2s, dt), dev(b2s), seed, ratio, W1, b1, W2, b2)
+    torch.cuda.synchronize()
+    for got, want in ((W1, ref[0]), (b1, ref[1]), (W2, ref[2]), (b2, ref[3])):
+        assert np.array_equal(H.np_of(got), np.asarray(want, np.float32))
+    # without biases: the weight outputs are the same, the bias outputs are not touched
+    W1b = torch.empty_like(W1); W2b = torch.empty_like(W2)
+    B.evomoe_diversify(ctx, shape, dev(W1s, dt), None, dev(W2s, dt), None, seed, ratio, W1b, None, W2b, None)
+    torch.cuda.synchronize()
+    assert torch.equal(W1b.view(torch.uint8), W1.view(torch.uint8)) and torch.equal(W2b.view(torch.uint8), W2.view(torch.uint8))
+    with pytest.raises(B.EvoMoEError) as e:
+        B.evomoe_diversify(ctx, shape, dev(W1s, dt), None, dev(W2s, dt), None, seed, 1.5, W1b, None, W2b, None)
+    assert e.value.status == B.EVOMOE_EINVAL

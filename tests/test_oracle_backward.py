@@ -11,7 +11,7 @@ import pytest
 import torch
 
 from oracle import evomoe_oracle as orc
-from paper_2112_14397_amd import synth
+import synth_inputs as synth
 
 
 def _case(T=10, d=6, E=4, F=12, act="gelu", seed=11):
@@ -223,5 +223,7 @@ def test_schedule_follows_the_papers_step_counts():
     taus = [orc.schedule(i, T_S, T_D).tau for i in range(5000, 10000)]
     assert all(a > b for a, b in zip(taus, taus[1:]))                       # strictly annealing
     assert np.allclose(np.diff(taus), np.diff(taus)[0])                     # evenly: a linear ramp
-    assert [round(orc.schedule(i, 0, 6).tau, 6) for i in range(6)] == [round(t, 6) for t in synth.linear_tau_schedule(6)]
+    # six evenly spaced temperatures between the paper's end points 2.0 and 0.3 (step 0.34), written out
+    assert [round(orc.schedule(i, 0, 6).tau, 6) for i in range(6)] == [2.0, 1.66, 1.32, 0.98, 0.64, 0.3]
+    assert orc.schedule(2500 + 5000 - 1, T_S, T_D).tau == pytest.approx(2.0 - 1.7 * 2499 / 4999)   # mid-ramp
     assert orc.schedule(7, 0, 1).top1 and orc.schedule(0, 0, 1).tau == 2.0

@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 from oracle import evomoe_oracle as orc
-from paper_2112_14397_amd import synth
+import synth_inputs as synth
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
