@@ -58,7 +58,8 @@ typedef enum {
     EVOMOE_EUNSUPPORTED = -2,  /* valid request outside the limits above */
     EVOMOE_ECAPACITY = -3,     /* P exceeded P_cap (reported by evomoe_num_pairs) */
     EVOMOE_EWORKSPACE = -4,    /* workspace too small / null */
-    EVOMOE_EHIP = -5           /* a HIP runtime call failed */
+    EVOMOE_EHIP = -5,          /* a HIP runtime call failed */
+    EVOMOE_ESTATIC = -6        /* evomoe_dispatch_static: the shape needs more than the library's static scratch */
 } evomoe_status;
 
 typedef enum { EVOMOE_F32 = 0, EVOMOE_BF16 = 1 } evomoe_dtype;
@@ -136,6 +137,20 @@ evomoe_status evomoe_dispatch(evomoe_ctx* ctx, const evomoe_shape* shape,
                               int32_t* expert_offsets, int32_t* pair_token, float* pair_gate,
                               int32_t* tok_off, int32_t* tok_rows, int64_t* num_pairs,
                               const void* x, void* x_perm, const int32_t* block_hist);
+
+/* evomoe_dispatch for callers that cannot allocate device memory at the moment of the call: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs and results as
+ * evomoe_dispatch without a block_hist table; the per-256-token histograms it counts go into a table that is part
+ * of the library image (256 KB on every GPU the library runs on, held until the process ends) instead of the
+ * context's scratch, which evomoe_dispatch may have to grow with a device allocation.  This call never allocates
+ * or frees.  Limit: ceil(T/256) * E <= 65536, else EVOMOE_ESTATIC and nothing is launched.  All calls on one GPU
+ * share the one table, whatever their context or stream: calls that overlap in time on one GPU race (calls on
+ * one stream do not overlap).  The table needs no clearing: every entry a call reads it has written before. */
+evomoe_status evomoe_dispatch_static(evomoe_ctx* ctx, const evomoe_shape* shape,
+                                     const uint64_t* mask_bits, const float* scores,
+                                     int32_t* expert_offsets, int32_t* pair_token, float* pair_gate,
+                                     int32_t* tok_off, int32_t* tok_rows, int64_t* num_pairs,
+                                     const void* x, void* x_perm);
 
 /* Expert FFNs forward over the ragged per-expert row ranges (Eq. ffn per expert e_i : R^D -> R^D).
  *   in : x [T,d] elem gathered through pair_token [P_cap], or, if pair_token == NULL, x is already

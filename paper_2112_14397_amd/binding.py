@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libevomoe.so")   # tests and tools may point thi
 EVOMOE_F32, EVOMOE_BF16 = 0, 1
 EVOMOE_RELU, EVOMOE_GELU_ERF = 0, 1
 EVOMOE_OK, EVOMOE_EINVAL, EVOMOE_EUNSUPPORTED, EVOMOE_ECAPACITY, EVOMOE_EWORKSPACE, EVOMOE_EHIP = 0, -1, -2, -3, -4, -5
+EVOMOE_ESTATIC = -6
 
 ENTRY_POINTS = (
     "evomoe_create", "evomoe_destroy", "evomoe_status_string", "evomoe_workspace_bytes",
@@ -27,7 +28,7 @@ ENTRY_POINTS = (
     "evomoe_num_pairs", "evomoe_profile_select", "evomoe_profile_read",
     "evomoe_dts_gate_top1", "evomoe_balance_loss", "evomoe_dts_gate_bwd_balance",
     "evomoe_workspace_bytes_recompute", "evomoe_expert_ffn_bwd_recompute", "evomoe_schedule",
-    "evomoe_hint_pairs", "evomoe_diversify",
+    "evomoe_hint_pairs", "evomoe_diversify", "evomoe_dispatch_static",
 )
 
 KERNEL_IDS = ("gate", "dispatch_hist", "dispatch_scatter", "ffn_gemm1", "ffn_gemm2", "combine", "combine_bwd",
@@ -73,6 +74,7 @@ def lib() -> ctypes.CDLL:
         L.evomoe_workspace_bytes.restype = sz
         L.evomoe_dts_gate.argtypes = [vp, sp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp, vp, vp]
         L.evomoe_dispatch.argtypes = [vp, sp] + [vp] * 11
+        L.evomoe_dispatch_static.argtypes = [vp, sp] + [vp] * 10
         L.evomoe_expert_ffn.argtypes = [vp, sp] + [vp] * 10
         L.evomoe_combine.argtypes = [vp, sp] + [vp] * 5
         L.evomoe_combine_bwd.argtypes = [vp, sp] + [vp] * 7
@@ -158,6 +160,13 @@ def evomoe_dispatch(ctx, shape, mask_bits, scores, expert_offsets, pair_token, p
     _chk(lib().evomoe_dispatch(ctx._h, ctypes.byref(shape), _p(mask_bits), _p(scores), _p(expert_offsets),
                                _p(pair_token), _p(pair_gate), _p(tok_off), _p(tok_rows), _p(num_pairs),
                                _p(x), _p(x_perm), _p(block_hist)), "evomoe_dispatch")
+
+
+def evomoe_dispatch_static(ctx, shape, mask_bits, scores, expert_offsets, pair_token, pair_gate, tok_off, tok_rows,
+                           num_pairs, x=None, x_perm=None):
+    _chk(lib().evomoe_dispatch_static(ctx._h, ctypes.byref(shape), _p(mask_bits), _p(scores), _p(expert_offsets),
+                                      _p(pair_token), _p(pair_gate), _p(tok_off), _p(tok_rows), _p(num_pairs),
+                                      _p(x), _p(x_perm)), "evomoe_dispatch_static")
 
 
 def evomoe_expert_ffn(ctx, shape, x, pair_token, expert_offsets, W1, b1, W2, b2, H, A, O):

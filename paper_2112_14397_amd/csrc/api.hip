@@ -104,6 +104,9 @@ evomoe_status evomoe_create(evomoe_ctx** ctx_out, void* hip_stream) {
         return EVOMOE_EHIP;
     }
     c.num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    // device address of the static histogram table of evomoe_dispatch_static, looked up once per device
+    c.static_hist = nullptr;
+    (void)static_hist_table(c.device, &c.static_hist);
     c.status_dev = small;          // [0] status flag
     if (hipMemsetAsync(small, 0, 256, c.stream) != hipSuccess ||
         ensure_scratch(c, 65536) != EVOMOE_OK) {
@@ -141,6 +144,8 @@ const char* evomoe_status_string(evomoe_status s) {
         case EVOMOE_ECAPACITY: return "number of selected pairs exceeds P_cap";
         case EVOMOE_EWORKSPACE: return "workspace missing or too small";
         case EVOMOE_EHIP: return "HIP runtime error";
+        case EVOMOE_ESTATIC: return "shape exceeds the static scratch of the entry point that allocates nothing "
+                                    "(ceil(T/256) * E > 65536)";
     }
     return "unknown status";
 }
@@ -204,7 +209,22 @@ evomoe_status evomoe_dispatch(evomoe_ctx* ctx, const evomoe_shape* shape, const 
         if (st != EVOMOE_OK) return st;
     }
     return from_hip(launch_dispatch(ctx->c, *shape, mask_bits, scores, block_hist, expert_offsets, pair_token,
-                                    pair_gate, tok_off, tok_rows, num_pairs, x, x_perm));
+                                    pair_gate, tok_off, tok_rows, num_pairs, x, x_perm, ctx->c.block_counts));
+}
+
+evomoe_status evomoe_dispatch_static(evomoe_ctx* ctx, const evomoe_shape* shape, const uint64_t* mask_bits,
+                                     const float* scores, int32_t* expert_offsets,
+                                     int32_t* pair_token, float* pair_gate, int32_t* tok_off, int32_t* tok_rows,
+                                     int64_t* num_pairs, const void* x, void* x_perm) {
+    CHECK_CTX_SHAPE();
+    REQUIRE_PTR(mask_bits); REQUIRE_PTR(scores); REQUIRE_PTR(expert_offsets); REQUIRE_PTR(pair_token);
+    REQUIRE_PTR(pair_gate); REQUIRE_PTR(tok_off); REQUIRE_PTR(tok_rows); REQUIRE_PTR(num_pairs);
+    OPTIONAL_PTR(x); OPTIONAL_PTR(x_perm);
+    if (x_perm && !x) return EVOMOE_EINVAL;
+    if ((size_t)dispatch_blocks(*shape) * shape->E > (size_t)kStaticHistEntries) return EVOMOE_ESTATIC;
+    if (!ctx->c.static_hist) return EVOMOE_EHIP;      // the address lookup at evomoe_create failed
+    return from_hip(launch_dispatch(ctx->c, *shape, mask_bits, scores, nullptr, expert_offsets, pair_token,
+                                    pair_gate, tok_off, tok_rows, num_pairs, x, x_perm, ctx->c.static_hist));
 }
 
 evomoe_status evomoe_expert_ffn(evomoe_ctx* ctx, const evomoe_shape* shape, const void* x,

@@ -9,6 +9,8 @@ namespace evomoe {
 
 constexpr int kWave = 64;                 // CDNA wavefront
 constexpr int kDispatchTokens = 256;      // tokens per dispatch block (one thread per token)
+constexpr int kStaticHistEntries = 65536; // ints in the static histogram table (256 KB per GPU): 1024 blocks x 64 experts
+constexpr int kMaxDevices = 64;
 
 typedef __bf16 bf16_t;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -105,6 +107,7 @@ struct Ctx {
     int64_t pair_hint;        // pair count announced by the caller (0 = none): picks tile shapes, nothing else
     int32_t* status_dev;      // [1] device flag: bit0 = capacity overflow
     int32_t* block_counts;    // scratch for per-block expert histograms
+    int32_t* static_hist;     // this device's address of the static table of evomoe_dispatch_static (or null)
     size_t block_counts_elems;
     uint16_t* wg_planes;      // bf16 gate: W_g split into three bf16 terms, transposed ([3][16*NE][d])
     size_t wg_planes_bytes;

@@ -8,6 +8,30 @@ namespace evomoe {
 
 int dispatch_blocks(const evomoe_shape& s) { return (s.T + kDispatchTokens - 1) / kDispatchTokens; }
 
+// Histogram table of the dispatch entry point that allocates nothing: device memory that exists from the moment
+// the library is loaded, one copy per GPU.  Host code never passes this name to a kernel (on the host it is only
+// a stand-in for the symbol); it asks the runtime once per device for the array's device address and uses that.
+static __device__ __align__(256) int32_t scratch[kStaticHistEntries];
+static int32_t* g_scratch_ptr[kMaxDevices];     // per device; null = not looked up yet
+
+hipError_t static_hist_table(int device, int32_t** table) {
+    *table = nullptr;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[device]) {
+        int cur = -1;
+        hipError_t e = hipGetDevice(&cur);
+        if (e != hipSuccess) return e;
+        if (cur != device) return hipErrorInvalidDevice;        // the lookup is made with that device current
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = static_cast<int32_t*>(p);
+    }
+    *table = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
 // Pass 1: per-block (256 consecutive tokens) expert histogram from wave ballots.
 __global__ __launch_bounds__(256) void dispatch_hist_kernel(
     const uint64_t* __restrict__ mask_bits, int T, int E, int32_t* __restrict__ block_counts)
@@ -176,14 +200,14 @@ hipError_t launch_gather_rows(const Ctx& c, const evomoe_shape& s, const void* x
 hipError_t launch_dispatch(const Ctx& c, const evomoe_shape& s, const uint64_t* mask_bits,
                            const float* scores, const int32_t* block_hist, int32_t* expert_offsets,
                            int32_t* pair_token, float* pair_gate, int32_t* tok_off, int32_t* tok_rows,
-                           int64_t* num_pairs, const void* x, void* x_perm) {
+                           int64_t* num_pairs, const void* x, void* x_perm, int32_t* hist_scratch) {
     const int nblk = dispatch_blocks(s);
     const int32_t* table = block_hist;
     if (!table) {       // the per-block histograms did not come with the mask: count them here
         ProfScope ps(c, EVOMOE_K_DISPATCH_HIST);
         hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(256), 0, c.stream, mask_bits, s.T, s.E,
-                           c.block_counts);
-        table = c.block_counts;
+                           hist_scratch);
+        table = hist_scratch;
     }
     {
         ProfScope ps(c, EVOMOE_K_DISPATCH_SCATTER);

@@ -24,8 +24,10 @@ hipError_t launch_balance_loss(const Ctx& c, const evomoe_shape& s, const float*
 hipError_t launch_dispatch(const Ctx& c, const evomoe_shape& s, const uint64_t* mask_bits,
                            const float* scores, const int32_t* block_hist, int32_t* expert_offsets,
                            int32_t* pair_token, float* pair_gate, int32_t* tok_off, int32_t* tok_rows,
-                           int64_t* num_pairs, const void* x, void* x_perm);
+                           int64_t* num_pairs, const void* x, void* x_perm, int32_t* hist_scratch);
 int dispatch_blocks(const evomoe_shape& s);     // 256-token groups: rows of a block_hist table
+// device address, on `device` (which must be current), of the library's static histogram table
+hipError_t static_hist_table(int device, int32_t** table);
 hipError_t launch_gather_rows(const Ctx& c, const evomoe_shape& s, const void* x, const int32_t* pair_token,
                               const int32_t* expert_offsets, void* x_perm);   // x_perm[r,:] = x[pair_token[r],:]
 hipError_t launch_dispatch_bwd(const Ctx& c, const evomoe_shape& s, const void* dXp,

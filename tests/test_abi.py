@@ -27,7 +27,7 @@ def test_library_exports_every_declared_entry_point():
 
 def test_status_strings_and_workspace_query():
     L = B.lib()
-    for s in (0, -1, -2, -3, -4, -5):
+    for s in (0, -1, -2, -3, -4, -5, -6):
         assert len(L.evomoe_status_string(s)) > 0
     ok = B.make_shape(8192, 768, 16, 3072, "bf16", "gelu", 8192 * 16)
     assert B.evomoe_workspace_bytes(ok) >= 8192 * 16 * 3072 * 2
