@@ -687,15 +687,28 @@ using CfgDh = CfgDuo;
 using CfgDx = CfgBig4;
 using CfgDw = CfgBig4;
 
-// The 256-row tiles pay off when there are enough of them for every compute unit and the experts' row ranges
-// are long enough not to be mostly padding; otherwise the 128-row tiles (two blocks per CU) are used.
-template <class Cfg> bool prefer_small_tiles(const Ctx& c, const evomoe_shape& s, int n) {
-    return expected_row_tiles<Cfg>(c, s) * ctiles<Cfg>(n) < (int64_t)c.num_cu * 3 / 2 ||
-           expected_pairs(c, s) / s.E < 3 * Cfg::BM;
+// Choice of tile shape per launch.  A persistent grid works through its tiles in rounds (one tile per resident
+// block), so a launch takes about rounds x (time of one tile): the finer 128-row tiles lose a little per flop but
+// waste less in the last, partly filled round and in the padding of each expert's last row tile.  The relative
+// tile times below were measured on the GPT-shaped layer (d = 768, F = 3072) at pair counts from 8 k to 58 k: a
+// 128x256x64 tile with a CU to itself takes 0.53 (NT) / 0.63 (NN) of a 256x256x32 tile; two co-resident 128x256x32
+// blocks take as long per round as one 256x256 block when the contraction is short (and 1.2x as long when it is
+// long, which never pays).  The weight-gradient launch and the act'(H) launch keep one shape each: 256x256 tiles
+// were 8-29 % faster than either 128-row shape for the former, and two co-resident blocks almost twice as fast
+// as a single 256x256 block for the latter.
+template <class Cfg> double launch_cost(const Ctx& c, const evomoe_shape& s, int n, double tile_time) {
+    const int64_t tiles = expected_row_tiles<Cfg>(c, s) * ctiles<Cfg>(n);
+    const int64_t slots = (int64_t)c.num_cu * Cfg::WPE;
+    return (double)((tiles + slots - 1) / slots) * tile_time;
 }
-// ... and among the 128-row configurations: LAT when (about) every tile gets a compute unit of its own
-inline bool prefer_fast_walk(const Ctx& c, const evomoe_shape& s, int n) {
-    return expected_row_tiles<CfgDuo>(c, s) * ctiles<CfgDuo>(n) <= (int64_t)c.num_cu * 5 / 4;
+enum class Tile { Big, Duo, Lat };
+// short contraction (GEMM1): 256-row tiles or two co-resident 128-row blocks
+inline Tile pick_short_k(const Ctx& c, const evomoe_shape& s, int n) {
+    return launch_cost<CfgDuo>(c, s, n, 1.0) < launch_cost<CfgBig4>(c, s, n, 1.0) ? Tile::Duo : Tile::Big;
+}
+// long contraction (GEMM2, dXp): 256-row tiles or 128-row tiles with 64-wide slabs, one block per CU
+inline Tile pick_long_k(const Ctx& c, const evomoe_shape& s, int n, double lat_time) {
+    return launch_cost<CfgLat>(c, s, n, lat_time) < launch_cost<CfgBig4>(c, s, n, 1.0) ? Tile::Lat : Tile::Big;
 }
 
 }  // namespace
@@ -718,7 +731,7 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
         a.A = (const bf16_t*)x; a.lda = s.d; a.a_rows = pair_token;
         a.B = (const bf16_t*)W1; a.ldb = s.d; a.b_group_stride = (int64_t)s.F * s.d;
         a.N = s.F; a.K = s.d; a.bias = b1; a.out1 = (bf16_t*)H; a.out2 = (bf16_t*)A;
-        if (prefer_small_tiles<Cfg>(c, s, s.F))
+        if (pick_short_k(c, s, s.F) == Tile::Duo)
             err = launch_gemm<L_NT, E_HA, CfgDuo>(c, a, row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(s.F));
         else
             err = launch_gemm<L_NT, E_HA, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.F));
@@ -730,10 +743,8 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
         a.A = (const bf16_t*)A; a.lda = s.F; a.a_rows = nullptr;
         a.B = (const bf16_t*)W2; a.ldb = s.F; a.b_group_stride = (int64_t)s.d * s.F;
         a.N = s.d; a.K = s.F; a.bias = b2; a.out1 = (bf16_t*)O; a.out2 = nullptr;
-        if (prefer_small_tiles<Cfg>(c, s, s.d) && prefer_fast_walk(c, s, s.d))
+        if (pick_long_k(c, s, s.d, 0.53) == Tile::Lat)
             err = launch_gemm<L_NT, E_BIAS, CfgLat>(c, a, row_tiles<CfgLat>(s) * ctiles<CfgLat>(s.d));
-        else if (prefer_small_tiles<Cfg>(c, s, s.d))
-            err = launch_gemm<L_NT, E_BIAS, CfgDuo>(c, a, row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(s.d));
         else
             err = launch_gemm<L_NT, E_BIAS, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.d));
     }
@@ -773,10 +784,8 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
         a.A = (const bf16_t*)dH; a.lda = s.F; a.B = (const bf16_t*)W1; a.ldb = s.d;
         a.b_group_stride = (int64_t)s.F * s.d; a.N = s.d; a.K = s.F; a.Hin = nullptr;
         a.out1 = (bf16_t*)dXp;
-        if (prefer_small_tiles<Cfg>(c, s, s.d) && prefer_fast_walk(c, s, s.d))
+        if (pick_long_k(c, s, s.d, 0.63) == Tile::Lat)
             err = launch_gemm<L_NN, E_NONE, CfgLat>(c, a, row_tiles<CfgLat>(s) * ctiles<CfgLat>(s.d));
-        else if (prefer_small_tiles<Cfg>(c, s, s.d))
-            err = launch_gemm<L_NN, E_NONE, CfgDuo>(c, a, row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(s.d));
         else
             err = launch_gemm<L_NN, E_NONE, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.d));
         if (err != hipSuccess) return err;
