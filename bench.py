@@ -232,8 +232,8 @@ def main():
                               "peak; frac = the larger of the two / measured step time"}
 
     out = {
-        "metric": "MoE-layer tokens/s fwd+bwd (d=768,E=16,T=8192) vs tau" if not top1 else
-                  "MoE-layer tokens/s fwd+bwd (d=768,E=16,T=8192), Top-1 steady state",
+        "metric": f"MoE-layer tokens/s fwd+bwd (d={cfg.d},E={cfg.E},T={cfg.T}) " + ("vs tau" if not top1 else
+                                                                                          "Top-1 steady state"),
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
