@@ -166,7 +166,7 @@ evomoe_status evomoe_dts_gate(evomoe_ctx* ctx, const evomoe_shape* shape, const 
     OPTIONAL_PTR(bg); OPTIONAL_PTR(noise); OPTIONAL_PTR(gate_w); OPTIONAL_PTR(k_per_token); OPTIONAL_PTR(block_hist);
     if (!(tau > 0.f) || !(threshold >= 0.f)) return EVOMOE_EINVAL;
     if (shape->dtype == EVOMOE_BF16) {
-        evomoe_status st = ensure_wg_planes(ctx->c, (size_t)3 * 64 * shape->d * sizeof(uint16_t));
+        evomoe_status st = ensure_wg_planes(ctx->c, (size_t)3 * 64 * ((shape->d + 31) / 32 * 32) * sizeof(uint16_t));
         if (st != EVOMOE_OK) return st;
     }
     return from_hip(launch_dts_gate(ctx->c, *shape, x, Wg, bg, noise, tau, threshold, gprime, gate_w,

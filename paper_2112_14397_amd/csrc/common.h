@@ -109,7 +109,7 @@ struct Ctx {
     int32_t* block_counts;    // scratch for per-block expert histograms
     int32_t* static_hist;     // this device's address of the static table of evomoe_dispatch_static (or null)
     size_t block_counts_elems;
-    uint16_t* wg_planes;      // bf16 gate: W_g split into three bf16 terms, transposed ([3][16*NE][d])
+    uint16_t* wg_planes;      // bf16 gate: W_g split into three bf16 terms, in MFMA fragment order
     size_t wg_planes_bytes;
     Prof* prof;
 };

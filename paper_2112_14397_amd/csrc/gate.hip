@@ -189,28 +189,35 @@ __global__ __launch_bounds__(256) void dts_gate_kernel(
 // bf16 layer.  x is exact in bf16, so W_g is split into three bf16 terms (hi + mid + lo carry all 24
 // mantissa bits of the float32 weight) and the logits come from three v_mfma_f32_16x16x32_bf16 per 32 k's:
 // every product is exact in float32 and the sum is accumulated in float32 -- the same accuracy as float32
-// FMAs, at matrix-core rate, which keeps the kernel HBM-bound up to E = 64.  The split, transposed copy of
-// W_g ([3][16*NE][d] bf16, zero rows beyond E) is made by gate_prep_kernel right before, which also clears the
-// integer sums the gate adds to (planes == null, float32 layer: clears only).
-__global__ __launch_bounds__(256) void gate_prep_kernel(const float* __restrict__ Wg, int d, int E, int EP,
+// FMAs, at matrix-core rate.  gate_prep_kernel makes the split copy right before, in the order the gate kernel's
+// lanes consume it: [k-block of 32][term][16-expert tile n][lane = 16 q + i16][8 k's], i.e. the B fragment of
+// one MFMA (expert 16 n + i16, k = 32 kb + 8 q .. +7) is 1 KB of consecutive memory, and the twelve fragments of
+// a k-block (E = 64) are 12 KB in a row: full cache lines, spread evenly over the L2 channels (rows of a plain
+// transposed copy are 2 d bytes apart, and every block of the grid asks for the same sixteen of them at the
+// same time).  Zero beyond E and beyond d.  The kernel also clears the integer sums the gate adds to
+// (planes == null, float32 layer: clears only).
+__global__ __launch_bounds__(256) void gate_prep_kernel(const float* __restrict__ Wg, int d, int E, int NE,
                                                         uint16_t* __restrict__ planes, int32_t* __restrict__ counts,
                                                         int32_t* __restrict__ block_hist, int n_hist)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;          // over EP * d, k fastest
+    const int i = blockIdx.x * 256 + threadIdx.x;          // over nkb * NE * 512 elements of one term, destination order
     if (i < E) counts[i] = 0;
     if (block_hist && i < n_hist) block_hist[i] = 0;
-    if (!planes || i >= EP * d) return;
-    const int e = i / d, k = i % d;
-    const float w = e < E ? Wg[(size_t)k * E + e] : 0.f;
+    const int nkb = (d + 31) / 32;
+    if (!planes || i >= nkb * NE * 512) return;
+    const int j = i & 7, lane = (i >> 3) & 63, n = (i >> 9) % NE, kb = (i >> 9) / NE;
+    const int e = n * 16 + (lane & 15), k = kb * 32 + (lane >> 4) * 8 + j;
+    const float w = (e < E && k < d) ? Wg[(size_t)k * E + e] : 0.f;
     const uint32_t hi = f32_to_bf16_bits(w);
     const float r1 = w - bf16_bits_to_f32(hi);
     const uint32_t mid = f32_to_bf16_bits(r1);
     const float r2 = r1 - bf16_bits_to_f32(mid);
     const uint32_t lo = f32_to_bf16_bits(r2);
-    const size_t plane = (size_t)EP * d;
-    planes[i] = (uint16_t)hi;
-    planes[plane + i] = (uint16_t)mid;
-    planes[2 * plane + i] = (uint16_t)lo;
+    // element (kb, term, n, lane, j)
+    const size_t base = ((size_t)kb * 3 * NE + n) * 512 + (size_t)lane * 8 + j;
+    planes[base] = (uint16_t)hi;
+    planes[base + (size_t)NE * 512] = (uint16_t)mid;
+    planes[base + (size_t)2 * NE * 512] = (uint16_t)lo;
 }
 
 template <int NE, int RT>
@@ -224,8 +231,6 @@ __global__ __launch_bounds__(256) void dts_gate_bf16_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i16 = lane & 15, q = lane >> 4;
     const int t0 = blockIdx.x * TPB;
-    const size_t plane = (size_t)EP * d;
-
     f32x4 acc[RT][NE];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
@@ -238,15 +243,13 @@ __global__ __launch_bounds__(256) void dts_gate_bf16_kernel(
     // W_g terms of the next k-block are fetched while the current one multiplies.
     constexpr int XU = RT * NE >= 8 ? 2 : (RT * NE >= 4 ? 4 : 8);
     auto load_planes = [&](int kb, bf16x8 (&b)[NE][3]) {
-        const int k0 = kb * 32 + q * 8;
-        const bool kok = k0 < d;
+        const bool kok = kb * 32 < d;
+        const bf16_t* wp = planes + ((size_t)(kok ? kb : 0) * 3 * NE) * 512 + lane * 8;
 #pragma unroll
-        for (int n = 0; n < NE; ++n) {
-            const bf16_t* wp = planes + (size_t)(n * 16 + i16) * d + (kok ? k0 : 0);
+        for (int n = 0; n < NE; ++n)
 #pragma unroll
             for (int pl = 0; pl < 3; ++pl)
-                b[n][pl] = kok ? *reinterpret_cast<const bf16x8*>(wp + pl * plane) : zero8;
-        }
+                b[n][pl] = kok ? *reinterpret_cast<const bf16x8*>(wp + (pl * NE + n) * 512) : zero8;
     };
     for (int kb0 = wave; kb0 * 32 < d; kb0 += 4 * XU) {
         bf16x8 a[XU][RT];
@@ -295,9 +298,9 @@ static hipError_t gate_launch_t(const Ctx& c, const evomoe_shape& s, const void*
     const int n_hist = dispatch_blocks(s) * s.E;
     ProfScope ps(c, EVOMOE_K_GATE);
     if constexpr (std::is_same<TX, bf16_t>::value) {
-        const int ep = 16 * NE;
-        const int n = ep * s.d > n_hist ? ep * s.d : n_hist;
-        hipLaunchKernelGGL(gate_prep_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, Wg, s.d, s.E, ep,
+        const int n_split = (s.d + 31) / 32 * NE * 512;
+        const int n = n_split > n_hist ? n_split : n_hist;
+        hipLaunchKernelGGL(gate_prep_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, Wg, s.d, s.E, NE,
                            c.wg_planes, counts, block_hist, n_hist);
         hipLaunchKernelGGL((dts_gate_bf16_kernel<NE, RT>), dim3(blocks), dim3(256), 0, c.stream,
                            (const bf16_t*)x, (const bf16_t*)c.wg_planes, bg, noise, tau, thr, s.T, s.d, s.E,
