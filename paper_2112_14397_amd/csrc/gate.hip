@@ -861,7 +861,16 @@ __global__ __launch_bounds__(64) void balance_final_kernel(const float* __restri
     const int e = threadIdx.x;
     float colsum = 0.f, cf = 0.f;
     if (e < E) {
-        for (int b = 0; b < nblk; ++b) colsum += partial[(size_t)b * E + e];
+        // block order, eight loads in flight at a time (the order of the additions does not change)
+        int b = 0;
+        for (; b + 8 <= nblk; b += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(b + u) * E + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) colsum += v[u];
+        }
+        for (; b < nblk; ++b) colsum += partial[(size_t)b * E + e];
         cf = alpha * (float)E * ((float)counts[e] / ((float)T * (float)T));
         if (coef) coef[e] = cf;
     }
