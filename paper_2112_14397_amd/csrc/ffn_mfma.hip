@@ -5,7 +5,7 @@
 //   NN  C[r,n] = sum_k A[r,k]       * W_g[k,n]      dH = dO W2,  dXp = dH W1
 //   TN  C_g[m,n] = sum_{r in g} L[r,m] * R[rrow(r),n]   weight gradients (contraction over the ragged rows)
 //
-// Block = 4 waves (2 x 2), block tile BM x BN, K slabs of BK, NSTAGE LDS stages filled by direct
+// Block = 4 waves (2 x 2) or 8 waves (4 x 2), block tile BM x BN, K slabs of BK, NSTAGE LDS stages filled by direct
 // global->LDS loads (no staging registers) that run NSTAGE-1 slabs ahead of the MFMAs.  Operands whose
 // contraction index is contiguous in memory sit in LDS as [row][BK k] with an XOR swizzle of the 16-byte
 // chunks and are read with ds_read_b128; operands whose contraction index is the row index sit as
@@ -41,7 +41,7 @@ struct GemmArgs {
     const float* row_scale;             // E_ACTGRAD: per-row factor applied in f32 before act' (or null)
     bf16_t* out1;                       // C (H for E_HA)
     bf16_t* out2;                       // E_HA: A = act(H)
-    float* colpart;                     // E_ACTGRAD: per-tile column sums of C, [row tile][2][N] (or null)
+    float* colpart;                     // E_ACTGRAD: per-tile column sums of C, [row tile][waves/2][N] (or null)
     int act, accumulate;
 };
 
@@ -55,17 +55,17 @@ struct GemmArgs {
 //  * k-strided tile [BK k][C cols] bf16, 2C B per row: 32-byte block b of row k sits at block
 //    b ^ 2(k & 3): the transposing read ds_read_b64_tr_b16 has 32 lanes take two adjacent blocks from
 //    four consecutive k rows, which then land in eight different 32-byte slots.
-template <int LAYOUT, int BM, int BN, int BK, int NSTAGE> struct Geo {
+template <int LAYOUT, int BM, int BN, int BK, int NSTAGE, int NW = 4> struct Geo {
     static constexpr bool A_KC = (LAYOUT != L_TN);          // A operand k-contiguous?
     static constexpr bool B_KC = (LAYOUT == L_NT);
     static constexpr int A_BYTES = BM * BK * 2;
     static constexpr int B_BYTES = BN * BK * 2;
     static constexpr int STAGE = A_BYTES + B_BYTES;
-    static constexpr int WM = BM / 2, WN = BN / 2;
+    static constexpr int WM = BM / (NW / 2), WN = BN / 2;       // waves: (NW/2) x 2
     static constexpr int EPI_LD = WN + 4;                    // f32 row stride of the staging copy
     // rows of the wave tile staged per pass: as many as fit next to nothing else in the operand stages
-    static constexpr int EPI_ROWS = (WM >= 64 && 4 * 64 * EPI_LD * 4 <= NSTAGE * STAGE + 8192) ? 64 : 32;
-    static constexpr int EPI_BYTES = 4 * EPI_ROWS * EPI_LD * 4;
+    static constexpr int EPI_ROWS = (WM >= 64 && NW * 64 * EPI_LD * 4 <= NSTAGE * STAGE + 8192) ? 64 : 32;
+    static constexpr int EPI_BYTES = NW * EPI_ROWS * EPI_LD * 4;
     static constexpr int MAIN = (NSTAGE * STAGE > EPI_BYTES ? NSTAGE * STAGE : EPI_BYTES);
     static constexpr int SMEM = MAIN;
 };
@@ -131,22 +131,23 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-template <int LAYOUT, int EPI, int BM, int BN, int BK, int NSTAGE, int WPE>
-__global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmArgs q1, int tiles0)
+template <int LAYOUT, int EPI, int BM, int BN, int BK, int NSTAGE, int WPE, int NW = 4>
+__global__ __launch_bounds__(NW * 64, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmArgs q1, int tiles0)
 {
     // TN launches carry two independent problems (dW2 and dW1) in one grid, tiles [0, tiles0) and
     // [tiles0, ...), which evens out the last round of the persistent schedule; other layouts use q0 only.
-    using G = Geo<LAYOUT, BM, BN, BK, NSTAGE>;
+    using G = Geo<LAYOUT, BM, BN, BK, NSTAGE, NW>;
     constexpr int WM = G::WM, WN = G::WN;
     constexpr int TM = WM / 32, TN_ = WN / 32;               // MFMA tiles per wave
     constexpr int KS = BK / 16;                              // k-steps per slab
-    constexpr int A_LD = G::A_BYTES / 4096, B_LD = G::B_BYTES / 4096;   // 1 KB load instructions per wave per slab
+    constexpr int A_LD = G::A_BYTES / (NW * 1024), B_LD = G::B_BYTES / (NW * 1024);   // 1 KB load instructions per wave per slab
     constexpr int KC_CH = BK / 8, KC_RPI = 64 / KC_CH;       // k-contiguous: 16 B chunks per row, rows per instruction
     constexpr int A_CPR = BM / 8, A_RPI = 64 / A_CPR;        // k-strided A: 16 B chunks per k-row, k-rows per instruction
     constexpr int B_CPR = BN / 8, B_RPI = 64 / B_CPR;
     constexpr int NMF = TM * TN_, NFR = TM + TN_, NLD = A_LD + B_LD;
     constexpr bool SPLIT_LD = NSTAGE >= 3;          // half of a slab's loads before the barrier, half after
     static_assert(BK == 32 || BK == 64, "slab");
+    static_assert(NW == 4 || NW == 8, "waves");
     static_assert(WM % 32 == 0 && WN % 32 == 0 && A_LD >= 1 && B_LD >= 1 && NSTAGE >= 2 && KS % 2 == 0, "tile");
     static_assert((NSTAGE - 2) * NLD + (NSTAGE - 1) * 2 <= 63, "vmcnt range");
 
@@ -244,11 +245,11 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
         // swizzle key of this lane's fragment rows (tile rows start at multiples of 32)
         const int sw = (BK == 64) ? ((l32 >> 1) & 7) : ((l32 >> 2) & 3);
 
-        // This lane's role in the 1 KB load instruction number (wave + 4*i) of a tile:
-        //   k-contiguous: row (wave+4i)*KC_RPI + lane/KC_CH, physical chunk lane%KC_CH -> logical chunk ^ key(row)
-        //   k-strided   : k-row (wave+4i)*RPI + lane/CPR, physical chunk lane%CPR -> logical chunk via block ^ (k & 3)
+        // This lane's role in the 1 KB load instruction number (wave + NW*i) of a tile (NW waves):
+        //   k-contiguous: row (wave+NW i)*KC_RPI + lane/KC_CH, physical chunk lane%KC_CH -> logical chunk ^ key(row)
+        //   k-strided   : k-row (wave+NW i)*RPI + lane/CPR, physical chunk lane%CPR -> logical chunk via block ^ (k & 3)
         const int kc_row = lane / KC_CH;
-        // key(row) of row (wave + 4i)*KC_RPI + kc_row does not depend on i
+        // key(row) of row (wave + NW i)*KC_RPI + kc_row does not depend on i
         const int kc_key = (BK == 64) ? ((4 * (wave & 1) + (kc_row >> 1)) & 7) : ((kc_row >> 2) & 3);
         const int kc_chunk = (lane % KC_CH) ^ kc_key;                           // logical 16 B chunk (8 k's)
         const int ksA_row = lane / A_CPR, ksB_row = lane / B_CPR;
@@ -268,7 +269,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             a_base = reinterpret_cast<const unsigned char*>(p.A) + (p.a_rows ? (int64_t)0 : (int64_t)row0 * p.lda * 2);
 #pragma unroll
             for (int i = 0; i < A_LD; ++i) {
-                const int r = min((wave + 4 * i) * KC_RPI + kc_row, rows - 1);
+                const int r = min((wave + NW * i) * KC_RPI + kc_row, rows - 1);
                 const uint32_t ar = p.a_rows ? (uint32_t)p.a_rows[row0 + r] : (uint32_t)r;
                 a_off[i] = (ar * (uint32_t)p.lda + kc_chunk * 8) * 2;
             }
@@ -280,7 +281,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             b_base = reinterpret_cast<const unsigned char*>(Bg);
 #pragma unroll
             for (int i = 0; i < B_LD; ++i) {
-                const int n = min(n0 + (wave + 4 * i) * KC_RPI + kc_row, p.N - 1);
+                const int n = min(n0 + (wave + NW * i) * KC_RPI + kc_row, p.N - 1);
                 b_off[i] = ((uint32_t)n * (uint32_t)p.ldb + kc_chunk * 8) * 2;
             }
         } else {
@@ -298,18 +299,18 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             if (idx < A_LD) {
                 const int i = idx;
                 if (G::A_KC) {
-                    load_to_lds(a_base, a_off[i] + (uint32_t)min(slab * (BK * 2), kc_lim), sa + i * 4096);
+                    load_to_lds(a_base, a_off[i] + (uint32_t)min(slab * (BK * 2), kc_lim), sa + i * (NW * 1024));
                 } else {
-                    const int kr = min(slab * BK + (wave + 4 * i) * A_RPI + ksA_row, klen - 1);
-                    load_to_lds(a_base, __umul24((uint32_t)kr, lda2) + a_col, sa + i * 4096);
+                    const int kr = min(slab * BK + (wave + NW * i) * A_RPI + ksA_row, klen - 1);
+                    load_to_lds(a_base, __umul24((uint32_t)kr, lda2) + a_col, sa + i * (NW * 1024));
                 }
             } else {
                 const int i = idx - A_LD;
                 if (G::B_KC) {
-                    load_to_lds(b_base, b_off[i] + (uint32_t)min(slab * (BK * 2), kc_lim), sb + i * 4096);
+                    load_to_lds(b_base, b_off[i] + (uint32_t)min(slab * (BK * 2), kc_lim), sb + i * (NW * 1024));
                 } else {
-                    const int kr = min(slab * BK + (wave + 4 * i) * B_RPI + ksB_row, klen - 1);
-                    load_to_lds(b_base, __umul24((uint32_t)kr, ldb2) + b_col, sb + i * 4096);
+                    const int kr = min(slab * BK + (wave + NW * i) * B_RPI + ksB_row, klen - 1);
+                    load_to_lds(b_base, __umul24((uint32_t)kr, ldb2) + b_col, sb + i * (NW * 1024));
                 }
             }
         };
@@ -328,13 +329,13 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
             if (G::A_KC) {
                 if (k0 + kc_chunk * 8 >= kend) {
 #pragma unroll
-                    for (int i = 0; i < A_LD; ++i) *reinterpret_cast<u32x4*>(sa + i * 4096 + lane * 16) = z;
+                    for (int i = 0; i < A_LD; ++i) *reinterpret_cast<u32x4*>(sa + i * (NW * 1024) + lane * 16) = z;
                 }
             } else {
 #pragma unroll
                 for (int i = 0; i < A_LD; ++i)
-                    if (k0 + (wave + 4 * i) * A_RPI + ksA_row >= kend)
-                        *reinterpret_cast<u32x4*>(sa + i * 4096 + lane * 16) = z;
+                    if (k0 + (wave + NW * i) * A_RPI + ksA_row >= kend)
+                        *reinterpret_cast<u32x4*>(sa + i * (NW * 1024) + lane * 16) = z;
             }
         };
         // operand fragment number f (A tiles 0..TM-1, then B tiles) of k-step ks of slab `slab`
@@ -583,7 +584,7 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
                     for (int q = 0; q < 8; ++q) cs[q] += __shfl_xor(cs[q], o, 64);
                 if (lane < CPW && col < p.N) {
                     const int rt = tstart[g] + (row0 - offs[g]) / BM;
-                    float* dst = p.colpart + ((int64_t)rt * 2 + wm) * p.N + col_c;
+                    float* dst = p.colpart + ((int64_t)rt * (NW / 2) + wm) * p.N + col_c;
                     *reinterpret_cast<f32x4*>(dst) = f32x4{cs[0], cs[1], cs[2], cs[3]};
                     *reinterpret_cast<f32x4*>(dst + 4) = f32x4{cs[4], cs[5], cs[6], cs[7]};
                 }
@@ -594,12 +595,12 @@ __global__ __launch_bounds__(256, WPE) void grouped_gemm_bf16(GemmArgs q0, GemmA
 }
 
 // Both bias gradients in one launch.  The first E * gx1 blocks (expert g = b / gx1, 256 columns each):
-// db1[g, n] (+)= sum over expert g's row tiles (two partial rows each) of the per-tile column sums written by the
+// db1[g, n] (+)= sum over expert g's row tiles (`parts` partial rows each) of the per-tile column sums written by the
 // dH GEMM, in row order.  The remaining blocks: db2[i] (+)= sum over the splits of the streaming column sums of
 // dO, in split order.  Reproducible bit for bit.
 __global__ __launch_bounds__(256) void bias_grad_final_kernel(
     const float* __restrict__ part1, const int32_t* __restrict__ expert_offsets, int E, int64_t P_cap, int N1,
-    int BM, int gx1, float* __restrict__ db1, const float* __restrict__ part2, size_t n2, float* __restrict__ db2,
+    int BM, int parts, int gx1, float* __restrict__ db1, const float* __restrict__ part2, size_t n2, float* __restrict__ db2,
     int accumulate)
 {
     if ((int)blockIdx.x >= E * gx1) {
@@ -625,32 +626,35 @@ __global__ __launch_bounds__(256) void bias_grad_final_kernel(
     int t0 = 0;                          // first row tile of expert g
     for (int e = 0; e < g; ++e) t0 += (offs[e + 1] - offs[e] + BM - 1) / BM;
     const int nt = (offs[g + 1] - offs[g] + BM - 1) / BM;
-    const float* src = part1 + (int64_t)t0 * 2 * N1 + n;
+    const float* src = part1 + (int64_t)t0 * parts * N1 + n;
     float sum = accumulate ? db1[(int64_t)g * N1 + n] : 0.f;
     int i = 0;
-    for (; i + 8 <= 2 * nt; i += 8) {
+    for (; i + 8 <= parts * nt; i += 8) {
         float v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(i + u) * N1];
 #pragma unroll
         for (int u = 0; u < 8; ++u) sum += v[u];
     }
-    for (; i < 2 * nt; ++i) sum += src[(int64_t)i * N1];
+    for (; i < parts * nt; ++i) sum += src[(int64_t)i * N1];
     db1[(int64_t)g * N1 + n] = sum;
 }
 
 // Tile configurations.  BIG4: one block per compute unit, 256 accumulator registers per lane.
+// OCT: the same tile and stages worked by eight waves (64x128 each, two per SIMD, 128 accumulator registers): 4 %
+// faster than BIG4 for GEMM1 and 1 % for the weight gradients, 2 % slower for GEMM2, the same for dXp.
 // DUO: two blocks per compute unit (one's epilogue and stalls hide under the other's MFMAs).
 // LAT: for launches with no more tiles than compute units and a long contraction: what counts then is how fast
 // one block walks its K loop, and 64-wide slabs halve the number of load/barrier rounds of that walk.
-struct CfgDuo { static constexpr int BM = 128, BN = 256, BK = 32, NSTAGE = 3, WPE = 2; };
-struct CfgBig4 { static constexpr int BM = 256, BN = 256, BK = 32, NSTAGE = 4, WPE = 1; };
-struct CfgLat { static constexpr int BM = 128, BN = 256, BK = 64, NSTAGE = 3, WPE = 1; };
+struct CfgDuo { static constexpr int BM = 128, BN = 256, BK = 32, NSTAGE = 3, WPE = 2, NW = 4; };
+struct CfgBig4 { static constexpr int BM = 256, BN = 256, BK = 32, NSTAGE = 4, WPE = 1, NW = 4; };
+struct CfgOct { static constexpr int BM = 256, BN = 256, BK = 32, NSTAGE = 4, WPE = 1, NW = 8; };
+struct CfgLat { static constexpr int BM = 128, BN = 256, BK = 64, NSTAGE = 3, WPE = 1, NW = 4; };
 
 template <int LAYOUT, int EPI, class Cfg>
 hipError_t launch_gemm(const Ctx& c, const GemmArgs& a0, int64_t tiles0, const GemmArgs& a1, int64_t tiles1) {
-    using G = Geo<LAYOUT, Cfg::BM, Cfg::BN, Cfg::BK, Cfg::NSTAGE>;
-    auto kern = grouped_gemm_bf16<LAYOUT, EPI, Cfg::BM, Cfg::BN, Cfg::BK, Cfg::NSTAGE, Cfg::WPE>;
+    using G = Geo<LAYOUT, Cfg::BM, Cfg::BN, Cfg::BK, Cfg::NSTAGE, Cfg::NW>;
+    auto kern = grouped_gemm_bf16<LAYOUT, EPI, Cfg::BM, Cfg::BN, Cfg::BK, Cfg::NSTAGE, Cfg::WPE, Cfg::NW>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -660,7 +664,7 @@ hipError_t launch_gemm(const Ctx& c, const GemmArgs& a0, int64_t tiles0, const G
     }
     const int64_t cap = (int64_t)c.num_cu * Cfg::WPE, worst = tiles0 + tiles1;
     const int grid = (int)(worst < cap ? worst : cap);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), G::SMEM, c.stream, a0, a1, (int)tiles0);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::NW * 64), G::SMEM, c.stream, a0, a1, (int)tiles0);
     return hipGetLastError();
 }
 template <int LAYOUT, int EPI, class Cfg>
@@ -681,11 +685,11 @@ template <class Cfg> int64_t expected_row_tiles(const Ctx& c, const evomoe_shape
     return (expected_pairs(c, s) + Cfg::BM - 1) / Cfg::BM + s.E / 2;
 }
 
-using CfgGemm1 = CfgBig4;
+using CfgGemm1 = CfgOct;
 using CfgGemm2 = CfgBig4;
 using CfgDh = CfgDuo;
 using CfgDx = CfgBig4;
-using CfgDw = CfgBig4;
+using CfgDw = CfgOct;
 
 // Choice of tile shape per launch.  A persistent grid works through its tiles in rounds (one tile per resident
 // block), so a launch takes about rounds x (time of one tile): the finer 128-row tiles lose a little per flop but
@@ -713,10 +717,10 @@ inline Tile pick_long_k(const Ctx& c, const evomoe_shape& s, int n, double lat_t
 
 }  // namespace
 
-// per-tile column sums of dH: two rows of F floats per row tile of the dH GEMM
+// per-tile column sums of dH: one row of F floats per wave row of each row tile of the dH GEMM
 size_t dh_colpart_bytes(const evomoe_shape& s) {
     if (s.dtype != EVOMOE_BF16) return 0;
-    return ((size_t)row_tiles<CfgDh>(s) * 2 * s.F * sizeof(float) + 255) & ~(size_t)255;
+    return ((size_t)row_tiles<CfgDh>(s) * (CfgDh::NW / 2) * s.F * sizeof(float) + 255) & ~(size_t)255;
 }
 
 hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, const int32_t* pair_token,
@@ -829,7 +833,7 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
         const size_t n2 = db2 ? (size_t)s.E * s.d : 0;
         const int gx1 = db1 ? (s.F + 255) / 256 : 0, gx2 = (int)((n2 + 255) / 256);
         hipLaunchKernelGGL(bias_grad_final_kernel, dim3(s.E * gx1 + gx2), dim3(256), 0, c.stream, colpart,
-                           expert_offsets, s.E, s.P_cap, s.F, (int)CfgDh::BM, gx1, db1, scratch, n2, db2,
+                           expert_offsets, s.E, s.P_cap, s.F, (int)CfgDh::BM, (int)CfgDh::NW / 2, gx1, db1, scratch, n2, db2,
                            accumulate);
         err = hipGetLastError();
     }
