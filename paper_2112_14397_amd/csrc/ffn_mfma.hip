@@ -43,6 +43,7 @@ struct GemmArgs {
     bf16_t* out2;                       // E_HA: A = act(H)
     float* colpart;                     // E_ACTGRAD: per-tile column sums of C, [row tile][waves/2][N] (or null)
     int act, accumulate;
+    int col_group;                      // NT/NN: column tiles per group of the tile order (1 .. all of them)
 };
 
 // ---- LDS geometry -------------------------------------------------------------------------------
@@ -173,13 +174,34 @@ __global__ __launch_bounds__(NW * 64, WPE) void grouped_gemm_bf16(GemmArgs q0, G
     }
     int cur_e = 0;                  // expert of the previous tile: row tiles only grow from tile to tile
 
-    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber the blocks so that
-    // one XCD works on a run of consecutive tiles (which share A row panels and B column panels) and the
-    // operands are fetched into that L2 once instead of into all eight.
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.
+    // TN: renumber the blocks so that one XCD works on a run of consecutive tiles per round (the tiles of one
+    // expert share its row range).
+    // NT/NN: the tile sequence runs expert by expert, inside an expert column group by column group (col_group
+    // column tiles whose weight panels fit the L2 together), inside a group row tile by row tile.  When the column
+    // tiles are split into groups, every XCD takes one contiguous eighth of that sequence and walks it round by
+    // round: the weight panels of a group are fetched into that XCD's L2 once and stay there while the expert's row
+    // panels stream past them.
+    const bool xcd_split = (gridDim.x & 7) == 0;
     int vblock = blockIdx.x;
-    if ((gridDim.x & 7) == 0) vblock = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    if (xcd_split) vblock = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    int seq = 0, seq_end = 0, seq_step = 0;
+    if (LAYOUT != L_TN) {
+        const int nct = (q0.N + BN - 1) / BN;
+        const int total = tstart[q0.E] * nct;
+        if (xcd_split && q0.col_group < nct) {
+            const int x = blockIdx.x & 7;
+            seq = (int)((int64_t)total * x / 8) + (blockIdx.x >> 3);
+            seq_end = (int)((int64_t)total * (x + 1) / 8);
+            seq_step = gridDim.x >> 3;
+        } else {            // one group holds every column tile: per round, a run of consecutive tiles per XCD
+            seq = vblock;
+            seq_end = total;
+            seq_step = gridDim.x;
+        }
+    }
 
-    for (int vtile = vblock;; vtile += gridDim.x) {
+    for (int vtile = vblock;; vtile += gridDim.x, seq += seq_step) {
         // ---------------- tile -> (problem, expert, origin, contraction range) ----------------
         const bool second = (LAYOUT == L_TN) && vtile >= tiles0;
         const GemmArgs& p = second ? q1 : q0;
@@ -196,12 +218,18 @@ __global__ __launch_bounds__(NW * 64, WPE) void grouped_gemm_bf16(GemmArgs q0, G
             kbeg = offs[g];
             kend = offs[g + 1];
         } else {
-            const int rt = tile / nct;
-            n0 = (tile % nct) * BN;
-            if (rt >= tstart[p.E]) break;
-            while (rt >= tstart[cur_e + 1]) ++cur_e;      // resumes where the previous tile's search ended
+            if (seq >= seq_end) break;
+            while (seq >= tstart[cur_e + 1] * nct) ++cur_e;      // resumes where the previous tile's search ended
             g = cur_e;
-            row0 = offs[g] + (rt - tstart[g]) * BM;
+            const int nrt = tstart[g + 1] - tstart[g];           // row tiles of this expert (>= 1 here)
+            const int r = seq - tstart[g] * nct;                 // position inside the expert's nrt * nct tiles
+            const int cgs = max(1, min(p.col_group, nct));       // column tiles per group
+            const int cg = r / (nrt * cgs);
+            const int r2 = r - cg * nrt * cgs;
+            const int gc = min(cgs, nct - cg * cgs);             // column tiles of this group (the last may be short)
+            const int rt_in = r2 / gc;
+            n0 = (cg * cgs + (r2 - rt_in * gc)) * BN;
+            row0 = offs[g] + rt_in * BM;
             rows = min(BM, offs[g + 1] - row0);
             kbeg = 0;
             kend = p.K;
@@ -691,6 +719,16 @@ using CfgDh = CfgDuo;
 using CfgDx = CfgBig4;
 using CfgDw = CfgOct;
 
+// Column tiles per group of the NT/NN tile order: as many weight panels (BN x K) as stay in one XCD's 4 MB L2 next to
+// the row panels streaming past them; all of them when a row panel (BM x K) is itself so large (long contractions)
+// that reading it once per group would cost more than re-reading the weights.
+template <class Cfg> int col_group_for(int n, int k) {
+    const int nct = (int)ctiles<Cfg>(n);
+    if ((int64_t)Cfg::BM * k * 2 >= (1 << 20)) return nct;
+    const int64_t fit = (int64_t)(2.4 * 1024 * 1024) / ((int64_t)Cfg::BN * k * 2);
+    return (int)(fit < 1 ? 1 : (fit > nct ? nct : fit));
+}
+
 // Choice of tile shape per launch.  A persistent grid works through its tiles in rounds (one tile per resident
 // block), so a launch takes about rounds x (time of one tile): the finer 128-row tiles lose a little per flop but
 // waste less in the last, partly filled round and in the padding of each expert's last row tile.  The relative
@@ -735,6 +773,7 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
         a.A = (const bf16_t*)x; a.lda = s.d; a.a_rows = pair_token;
         a.B = (const bf16_t*)W1; a.ldb = s.d; a.b_group_stride = (int64_t)s.F * s.d;
         a.N = s.F; a.K = s.d; a.bias = b1; a.out1 = (bf16_t*)H; a.out2 = (bf16_t*)A;
+        a.col_group = col_group_for<Cfg>(s.F, s.d);
         if (pick_short_k(c, s, s.F) == Tile::Duo)
             err = launch_gemm<L_NT, E_HA, CfgDuo>(c, a, row_tiles<CfgDuo>(s) * ctiles<CfgDuo>(s.F));
         else
@@ -747,6 +786,7 @@ hipError_t mfma_ffn_fwd(const Ctx& c, const evomoe_shape& s, const void* x, cons
         a.A = (const bf16_t*)A; a.lda = s.F; a.a_rows = nullptr;
         a.B = (const bf16_t*)W2; a.ldb = s.F; a.b_group_stride = (int64_t)s.d * s.F;
         a.N = s.d; a.K = s.F; a.bias = b2; a.out1 = (bf16_t*)O; a.out2 = nullptr;
+        a.col_group = col_group_for<Cfg>(s.d, s.F);
         if (pick_long_k(c, s, s.d, 0.53) == Tile::Lat)
             err = launch_gemm<L_NT, E_BIAS, CfgLat>(c, a, row_tiles<CfgLat>(s) * ctiles<CfgLat>(s.d));
         else
@@ -778,6 +818,7 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
         a.B = (const bf16_t*)W2; a.ldb = s.F;
         a.b_group_stride = (int64_t)s.d * s.F; a.N = s.F; a.K = s.d; a.Hin = (const bf16_t*)H;
         a.out1 = (bf16_t*)dH; a.colpart = db1 ? colpart : nullptr;
+        a.col_group = col_group_for<Cfg>(s.F, s.d);
         err = launch_gemm<L_NN, E_ACTGRAD, Cfg>(c, a, row_tiles<Cfg>(s) * ctiles<Cfg>(s.F));
         a.colpart = nullptr; a.a_rows = nullptr; a.row_scale = nullptr;
         if (err != hipSuccess) return err;
@@ -788,6 +829,7 @@ hipError_t mfma_ffn_bwd(const Ctx& c, const evomoe_shape& s, const void* dO, con
         a.A = (const bf16_t*)dH; a.lda = s.F; a.B = (const bf16_t*)W1; a.ldb = s.d;
         a.b_group_stride = (int64_t)s.F * s.d; a.N = s.d; a.K = s.F; a.Hin = nullptr;
         a.out1 = (bf16_t*)dXp;
+        a.col_group = col_group_for<Cfg>(s.d, s.F);
         if (pick_long_k(c, s, s.d, 0.63) == Tile::Lat)
             err = launch_gemm<L_NN, E_NONE, CfgLat>(c, a, row_tiles<CfgLat>(s) * ctiles<CfgLat>(s.d));
         else
