@@ -734,10 +734,11 @@ template <class Cfg> int col_group_for(int n, int k) {
 // waste less in the last, partly filled round and in the padding of each expert's last row tile.  The relative
 // tile times below were measured on the GPT-shaped layer (d = 768, F = 3072) at pair counts from 8 k to 58 k: a
 // 128x256x64 tile with a CU to itself takes 0.53 (NT) / 0.63 (NN) of a 256x256x32 tile; two co-resident 128x256x32
-// blocks take 1.06 times as long per round as one 256x256 block when the contraction is short (and 1.2x as long when
-// it is long, which never pays).  The weight-gradient launch and the act'(H) launch keep one shape each: 256x256 tiles
-// were 8-29 % faster than either 128-row shape for the former, and for the latter two co-resident blocks are almost
-// twice as fast as a four-wave 256x256 block and 2 % faster than an eight-wave one.
+// blocks take 1.06-1.2 times as long per round as one eight-wave 256x256 block when the contraction is short
+// (priced at 1.15; 1.2x and more when it is long, which never pays).  The weight-gradient launch and the act'(H)
+// launch keep one shape each: 256x256 tiles were 8-29 % faster than either 128-row shape for the former, and for
+// the latter two co-resident blocks are almost twice as fast as a four-wave 256x256 block and 2 % faster than an
+// eight-wave one.
 template <class Cfg> double launch_cost(const Ctx& c, const evomoe_shape& s, int n, double tile_time) {
     const int64_t tiles = expected_row_tiles<Cfg>(c, s) * ctiles<Cfg>(n);
     const int64_t slots = (int64_t)c.num_cu * Cfg::WPE;
@@ -746,7 +747,7 @@ template <class Cfg> double launch_cost(const Ctx& c, const evomoe_shape& s, int
 enum class Tile { Big, Duo, Lat };
 // short contraction (GEMM1): 256-row tiles or two co-resident 128-row blocks
 inline Tile pick_short_k(const Ctx& c, const evomoe_shape& s, int n) {
-    return launch_cost<CfgDuo>(c, s, n, 1.06) < launch_cost<CfgGemm1>(c, s, n, 1.0) ? Tile::Duo : Tile::Big;
+    return launch_cost<CfgDuo>(c, s, n, 1.15) < launch_cost<CfgGemm1>(c, s, n, 1.0) ? Tile::Duo : Tile::Big;
 }
 // long contraction (GEMM2, dXp): 256-row tiles or 128-row tiles with 64-wide slabs, one block per CU
 inline Tile pick_long_k(const Ctx& c, const evomoe_shape& s, int n, double lat_time) {
