@@ -118,6 +118,25 @@ def test_expert_with_no_tokens_and_skewed_load():
     assert not h.np_of(gl.buf.dW1)[2].any() and not h.np_of(gl.buf.dW2)[5].any()
 
 
+def test_full_width_layer_with_empty_experts_takes_the_grouped_tile_order():
+    """d = 768, F = 3072 as in configs 2 and 3, few tokens: the launches fill the whole persistent grid, GEMM1 and dH
+    walk their tiles expert by expert in column groups with one share of the sequence per XCD, and two experts
+    have no rows at all (their tile ranges are empty and must be stepped over)."""
+    h = _harness()
+    cfg, inp = _mk("wide", 1536, 768, 16, 3072, "gelu", "bf16", 0.05, 207, gate_scale=3.0)
+    bg = np.zeros(16, np.float32)
+    bg[[2, 11]] = -60.0                                             # never selected
+    bg[7] = 2.0                                                     # selected by almost every token
+    inp.bg = bg
+    gl = h.GpuLayer(inp)
+    fwd, P, band, flip = h.compare_forward(gl, inp, 1.0, 0.05)
+    cnt = h.np_of(gl.buf.counts)
+    assert cnt[2] == 0 and cnt[11] == 0 and cnt[7] > 2 * np.median(cnt)
+    assert P > 3000                                                 # several row tiles per expert
+    h.compare_backward(gl, inp, fwd, 1.0, dx_tail=h.DX_TAIL)
+    assert not h.np_of(gl.buf.dW1)[2].any() and not h.np_of(gl.buf.dW2)[11].any()
+
+
 def test_no_noise_no_bias_pointers():
     h = _harness()
     cfg, inp = _mk("nonoise", 200, 64, 4, 128, "relu", "f32", 0.1, 205, bias=0.0, gate_scale=20.0)
